@@ -1,0 +1,174 @@
+/*
+ * s2attn - head-heterogeneous block-sparse causal attention for AMD MI355X (gfx950).
+ *
+ * C ABI of libs2attn.so.  Every pointer is marked HOST or DEVICE.  bf16 tensors are
+ * raw 16-bit patterns (void*); LSE and workspaces are float / bytes.  The library
+ * never takes ownership of a tensor or workspace; it owns only the index arrays
+ * inside an s2_layout handle.  All launches are asynchronous on the stream passed
+ * in (a hipStream_t cast to void*, NULL = the default stream); no call synchronises
+ * the device except s2_layout_build/destroy (one upload / free of small arrays).
+ *
+ * Every function returns an int status: S2_OK (0) or a negative S2_ERR_* code.
+ * Arguments are validated before anything is launched; on error no output is
+ * written.  No C++ exception crosses this boundary.
+ *
+ * Vocabulary (the paper's): a sequence of N tokens is cut into B = ceil(N/S) shards
+ * ("blocks") of S consecutive tokens (section 3.2).  Head h has a B x B block mask
+ * M^h (section 4.2): block row i keeps block column j when
+ *     0 <= i-j < B_l                                        (local), or
+ *     j-o_h in {0, s, 2s, ...}  and  B_l <= i-j             (stride),
+ * where o_h = (head_index_base + h) mod s.  If window_blocks > 0 the stride case
+ * also requires i-j < window_blocks (the paper's upper bound on i-j).  Inside the
+ * diagonal block the token mask is causal (key position <= query position); all
+ * other kept blocks are fully visible.
+ */
+#ifndef S2ATTN_H
+#define S2ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  S2_OK = 0,
+  S2_ERR_NULL = -1,       /* a required pointer is NULL                                  */
+  S2_ERR_BAD_PARAM = -2,  /* layout parameter out of range (B_l < 1, stride < 0, ...)    */
+  S2_ERR_SHAPE = -3,      /* tensor shape does not fit the layout / unsupported head_dim */
+  S2_ERR_ALIGN = -4,      /* pointer or stride not 16-byte aligned                       */
+  S2_ERR_WORKSPACE = -5,  /* workspace missing or too small                              */
+  S2_ERR_HIP = -6,        /* a HIP runtime call failed; see s2_last_hip_error()          */
+  S2_ERR_NO_DEVICE = -7,  /* layout was built without a GPU and a launch was requested   */
+  S2_ERR_OVERFLOW = -8    /* index arrays would not fit in int32                         */
+};
+
+/* Parameters of the per-head block mask of section 4.2.  Plain integers, HOST. */
+typedef struct {
+  int32_t num_heads;       /* H: heads covered by this layout (>= 1)                          */
+  int32_t head_index_base; /* global index of local head 0; o_h uses the global index (>= 0)  */
+  int32_t num_blocks;      /* B = N / S (>= 1)                                                */
+  int32_t block_size;      /* S in tokens: 64 or 128                                          */
+  int32_t local_blocks;    /* B_l >= 1; counts the diagonal block                             */
+  int32_t stride;          /* s >= 0; 0 = no stripes (pure sliding window)                    */
+  int32_t window_blocks;   /* upper bound on i-j for stripes; 0 = unbounded                   */
+  int32_t dense;           /* 1 = every causal block kept (the three fields above ignored)    */
+} s2_layout_params;
+
+/* Opaque handle: the compressed mask (host and device copies) and the kernels' tile lists. */
+typedef struct s2_layout s2_layout;
+
+/* Read-only HOST view of a layout.  Canonical form: rows ordered head-major then block-row,
+ * columns strictly ascending inside a row, row_ptr[h*B+i] a global offset into col_idx
+ * (compressed sparse row, section 3.2).  col_ptr/row_idx are the exact transpose (per head,
+ * per block column, ascending rows).  Pointers stay valid until s2_layout_destroy. */
+typedef struct {
+  const int32_t* row_ptr;  /* [H*B+1] */
+  const int32_t* col_idx;  /* [nnz]   */
+  const int32_t* col_ptr;  /* [H*B+1] */
+  const int32_t* row_idx;  /* [nnz]   */
+  int64_t nnz;             /* kept blocks summed over heads                                   */
+  int32_t num_heads, num_blocks, block_size;
+  int32_t max_row_blocks;  /* longest row                                                     */
+  int32_t covers_all;      /* 1 iff the union over heads keeps every causal block (sec. 4.2)  */
+  int32_t on_device;       /* 1 iff the device copies exist                                   */
+} s2_layout_view;
+
+/* Training-path tensors.  All bf16 tensors are [batch, heads, seqlen, head_dim] addressed as
+ * base + b*stride_b + h*stride_h + t*stride_t + d (strides in ELEMENTS, head_dim contiguous).
+ * q, o, d_o, dq share the q_* strides; k, v, dk, dv share the kv_* strides.  Strides must be
+ * multiples of 8 elements and base pointers 16-byte aligned.  lse is contiguous fp32
+ * [batch, heads, seqlen].  Pointers not used by a call may be NULL. */
+typedef struct {
+  const void* q;    /* DEVICE bf16, in                    */
+  const void* k;    /* DEVICE bf16, in                    */
+  const void* v;    /* DEVICE bf16, in                    */
+  void* o;          /* DEVICE bf16, fwd out / bwd in      */
+  float* lse;       /* DEVICE fp32, fwd out / bwd in      */
+  const void* d_o;  /* DEVICE bf16, bwd in                */
+  void* dq;         /* DEVICE bf16, bwd out               */
+  void* dk;         /* DEVICE bf16, bwd out               */
+  void* dv;         /* DEVICE bf16, bwd out               */
+  int32_t batch, heads, seqlen, head_dim; /* head_dim 64 or 128; seqlen == B*S            */
+  int64_t q_stride_b, q_stride_h, q_stride_t;
+  int64_t kv_stride_b, kv_stride_h, kv_stride_t;
+} s2_tensors;
+
+/* Decode: nseq sequences, one query token each (the token at position len-1, whose key and
+ * value are already in the cache), against a contiguous bf16 KV cache (section 4.1). */
+typedef struct {
+  const void* q;            /* DEVICE bf16 [nseq, heads, head_dim], contiguous               */
+  const void* k_cache;      /* DEVICE bf16, element (b,h,t,d) at b*sb + h*sh + t*st + d      */
+  const void* v_cache;      /* DEVICE bf16, same strides                                     */
+  const int32_t* seq_lens;  /* DEVICE int32 [nseq], each in [1, max_len]                     */
+  void* o;                  /* DEVICE bf16 [nseq, heads, head_dim], out                      */
+  float* lse;               /* DEVICE fp32 [nseq, heads], out (may be NULL)                  */
+  int32_t nseq, heads, head_dim; /* head_dim 64 or 128                                      */
+  int32_t max_len;          /* upper bound on seq_lens, sizes the launch                     */
+  int32_t num_splits;       /* KV splits per (sequence, head); 0 = library chooses           */
+  int64_t kv_stride_seq, kv_stride_head, kv_stride_tok; /* elements, multiples of 8          */
+} s2_decode_args;
+
+/* ---- layout (section 4.2 mask -> compressed lists, section 3.2) ------------------------- */
+
+/* Builds the per-head lists of kept KV blocks from the closed form of the mask, on the host,
+ * and, when a GPU is visible, uploads them to the current device.  *out is owned by the
+ * caller until s2_layout_destroy.  Errors: NULL, BAD_PARAM (H<1, B<1, S not 64/128, B_l<1,
+ * stride<0, window<0, head_index_base<0), OVERFLOW, HIP. */
+int s2_layout_build(const s2_layout_params* params, s2_layout** out);
+int s2_layout_destroy(s2_layout* layout);
+int s2_layout_get(const s2_layout* layout, s2_layout_view* out);
+
+/* ---- forward (section 3.2: softmax over the kept keys only) ------------------------------ */
+
+/* O = softmax(scale * Q K^T restricted to the mask) V, LSE = natural-log sum-exp of the scaled
+ * kept scores.  Reads q,k,v; writes o (bf16) and lse (fp32).  scale must be > 0.
+ * Requires t->heads == layout heads and t->seqlen == B*S.  Errors: NULL, SHAPE, ALIGN,
+ * BAD_PARAM (scale), NO_DEVICE, HIP. */
+int s2_attn_fwd(const s2_layout* layout, const s2_tensors* t, float scale, void* stream);
+
+/* ---- backward (gradient of the above) ---------------------------------------------------- */
+
+/* Given q,k,v,o,lse,d_o writes dq,dk,dv (bf16; fp32 accumulation).  workspace is DEVICE memory
+ * of at least s2_attn_bwd_workspace_bytes(...) bytes, 256-byte aligned, contents undefined on
+ * entry and exit.  Errors as forward plus WORKSPACE. */
+int s2_attn_bwd(const s2_layout* layout, const s2_tensors* t, float scale, void* workspace,
+                size_t workspace_bytes, void* stream);
+size_t s2_attn_bwd_workspace_bytes(int32_t batch, int32_t heads, int32_t seqlen, int32_t head_dim);
+
+/* ---- dense causal attention: the in-library speed baseline ------------------------------- */
+
+/* Same tensors and outputs as s2_attn_fwd / s2_attn_bwd with every causal key kept; the block
+ * loop is arithmetic (no index lists, no layout handle).  seqlen must be a multiple of 128. */
+int s2_dense_causal_fwd(const s2_tensors* t, float scale, void* stream);
+int s2_dense_causal_bwd(const s2_tensors* t, float scale, void* workspace, size_t workspace_bytes,
+                        void* stream);
+
+/* ---- decode (section 4.1: one step against the cache) ------------------------------------ */
+
+/* For sequence b with length L = seq_lens[b]: the query attends, among the first L cached
+ * tokens, the blocks kept in block row (L-1) div S of the mask for ceil(L/S) blocks (the last
+ * block may be partial).  The KV range is cut into num_splits pieces whose partial
+ * (max, sum, accumulator) triples go to workspace and are merged by a second kernel.
+ * p->num_heads must equal a->heads; p->num_blocks is ignored.  Errors: NULL, BAD_PARAM, SHAPE,
+ * ALIGN, WORKSPACE, HIP. */
+int s2_attn_decode(const s2_layout_params* p, const s2_decode_args* a, float scale,
+                   void* workspace, size_t workspace_bytes, void* stream);
+size_t s2_attn_decode_workspace_bytes(int32_t nseq, int32_t heads, int32_t head_dim,
+                                      int32_t max_len, int32_t num_splits);
+/* The split count the library would pick for num_splits == 0. */
+int32_t s2_attn_decode_default_splits(int32_t nseq, int32_t heads, int32_t max_len);
+
+/* ---- diagnostics -------------------------------------------------------------------------- */
+
+const char* s2_status_string(int status);
+/* hipError_t (as int) of the most recent failing HIP call on this thread, 0 if none. */
+int s2_last_hip_error(void);
+/* Library version, e.g. 100 = 0.1.0. */
+int s2_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* S2ATTN_H */

@@ -1,0 +1,229 @@
+"""ctypes binding of libs2attn.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (see
+``include/s2attn.h``) and does nothing but turn torch tensors into pointers,
+sizes and strides.  torch is used for device memory and streams; all of the
+attention arithmetic runs inside the HIP library.  There is no fallback: if
+the shared library is missing, importing this module raises.
+"""
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libs2attn.so")
+
+S2_OK = 0
+STATUS_NAMES = {
+    0: "S2_OK", -1: "S2_ERR_NULL", -2: "S2_ERR_BAD_PARAM", -3: "S2_ERR_SHAPE", -4: "S2_ERR_ALIGN",
+    -5: "S2_ERR_WORKSPACE", -6: "S2_ERR_HIP", -7: "S2_ERR_NO_DEVICE", -8: "S2_ERR_OVERFLOW",
+}
+
+
+class S2Error(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = "%s failed: %s (%s)" % (where, STATUS_NAMES.get(status, status),
+                                      lib().s2_status_string(status).decode())
+        if status == -6:
+            msg += " hipError=%d" % lib().s2_last_hip_error()
+        super().__init__(msg)
+
+
+class LayoutParams(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "num_heads", "head_index_base", "num_blocks", "block_size", "local_blocks", "stride",
+        "window_blocks", "dense")]
+
+
+class LayoutView(C.Structure):
+    _fields_ = [("row_ptr", C.POINTER(C.c_int32)), ("col_idx", C.POINTER(C.c_int32)),
+                ("col_ptr", C.POINTER(C.c_int32)), ("row_idx", C.POINTER(C.c_int32)),
+                ("nnz", C.c_int64), ("num_heads", C.c_int32), ("num_blocks", C.c_int32),
+                ("block_size", C.c_int32), ("max_row_blocks", C.c_int32), ("covers_all", C.c_int32),
+                ("on_device", C.c_int32)]
+
+
+class Tensors(C.Structure):
+    _fields_ = [("q", C.c_void_p), ("k", C.c_void_p), ("v", C.c_void_p), ("o", C.c_void_p),
+                ("lse", C.c_void_p), ("d_o", C.c_void_p), ("dq", C.c_void_p), ("dk", C.c_void_p),
+                ("dv", C.c_void_p),
+                ("batch", C.c_int32), ("heads", C.c_int32), ("seqlen", C.c_int32), ("head_dim", C.c_int32),
+                ("q_stride_b", C.c_int64), ("q_stride_h", C.c_int64), ("q_stride_t", C.c_int64),
+                ("kv_stride_b", C.c_int64), ("kv_stride_h", C.c_int64), ("kv_stride_t", C.c_int64)]
+
+
+class DecodeArgs(C.Structure):
+    _fields_ = [("q", C.c_void_p), ("k_cache", C.c_void_p), ("v_cache", C.c_void_p),
+                ("seq_lens", C.c_void_p), ("o", C.c_void_p), ("lse", C.c_void_p),
+                ("nseq", C.c_int32), ("heads", C.c_int32), ("head_dim", C.c_int32),
+                ("max_len", C.c_int32), ("num_splits", C.c_int32),
+                ("kv_stride_seq", C.c_int64), ("kv_stride_head", C.c_int64), ("kv_stride_tok", C.c_int64)]
+
+
+EXPORTS = (
+    "s2_layout_build", "s2_layout_destroy", "s2_layout_get", "s2_attn_fwd", "s2_attn_bwd",
+    "s2_attn_bwd_workspace_bytes", "s2_dense_causal_fwd", "s2_dense_causal_bwd", "s2_attn_decode",
+    "s2_attn_decode_workspace_bytes", "s2_attn_decode_default_splits", "s2_status_string",
+    "s2_last_hip_error", "s2_version",
+)
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library (loads it on first use; raises if it has not been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libs2attn.so is not built: run `python -m paper_2407_17678_amd.build`")
+    L = C.CDLL(LIB_PATH)
+    L.s2_layout_build.argtypes = [C.POINTER(LayoutParams), C.POINTER(C.c_void_p)]
+    L.s2_layout_destroy.argtypes = [C.c_void_p]
+    L.s2_layout_get.argtypes = [C.c_void_p, C.POINTER(LayoutView)]
+    L.s2_attn_fwd.argtypes = [C.c_void_p, C.POINTER(Tensors), C.c_float, C.c_void_p]
+    L.s2_attn_bwd.argtypes = [C.c_void_p, C.POINTER(Tensors), C.c_float, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.s2_attn_bwd_workspace_bytes.argtypes = [C.c_int32] * 4
+    L.s2_attn_bwd_workspace_bytes.restype = C.c_size_t
+    L.s2_dense_causal_fwd.argtypes = [C.POINTER(Tensors), C.c_float, C.c_void_p]
+    L.s2_dense_causal_bwd.argtypes = [C.POINTER(Tensors), C.c_float, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.s2_attn_decode.argtypes = [C.POINTER(LayoutParams), C.POINTER(DecodeArgs), C.c_float, C.c_void_p,
+                                 C.c_size_t, C.c_void_p]
+    L.s2_attn_decode_workspace_bytes.argtypes = [C.c_int32] * 5
+    L.s2_attn_decode_workspace_bytes.restype = C.c_size_t
+    L.s2_attn_decode_default_splits.argtypes = [C.c_int32] * 3
+    L.s2_attn_decode_default_splits.restype = C.c_int32
+    L.s2_status_string.argtypes = [C.c_int]
+    L.s2_status_string.restype = C.c_char_p
+    L.s2_last_hip_error.restype = C.c_int
+    L.s2_version.restype = C.c_int
+    for name in EXPORTS:
+        getattr(L, name)
+    _lib = L
+    return L
+
+
+def _check(status, where):
+    if status != S2_OK:
+        raise S2Error(status, where)
+
+
+def _stream_ptr(stream):
+    """torch stream (or None = torch's current stream) -> hipStream_t as an integer."""
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def layout_params(num_heads, num_blocks, block_size, local_blocks, stride, head_index_base=0,
+                  window_blocks=0, dense=0):
+    return LayoutParams(num_heads, head_index_base, num_blocks, block_size, local_blocks, stride,
+                        window_blocks, dense)
+
+
+class Layout:
+    """Owner of an s2_layout handle."""
+
+    def __init__(self, handle, params):
+        self.handle = handle
+        self.params = params
+
+    def __del__(self):
+        h, self.handle = getattr(self, "handle", None), None
+        if h and _lib is not None:
+            _lib.s2_layout_destroy(h)
+
+
+def s2_layout_build(params):
+    out = C.c_void_p()
+    _check(lib().s2_layout_build(C.byref(params), C.byref(out)), "s2_layout_build")
+    return Layout(out, params)
+
+
+def s2_layout_destroy(layout):
+    h, layout.handle = layout.handle, None
+    if h:
+        _check(lib().s2_layout_destroy(h), "s2_layout_destroy")
+
+
+def s2_layout_get(layout):
+    """Host copies of the canonical arrays as numpy int32, plus the scalar fields."""
+    v = LayoutView()
+    _check(lib().s2_layout_get(layout.handle, C.byref(v)), "s2_layout_get")
+    n = v.num_heads * v.num_blocks + 1
+    as_np = lambda p, k: np.ctypeslib.as_array(p, shape=(k,)).copy() if k else np.zeros(0, np.int32)
+    return {
+        "row_ptr": as_np(v.row_ptr, n), "col_idx": as_np(v.col_idx, v.nnz),
+        "col_ptr": as_np(v.col_ptr, n), "row_idx": as_np(v.row_idx, v.nnz),
+        "nnz": v.nnz, "num_heads": v.num_heads, "num_blocks": v.num_blocks,
+        "block_size": v.block_size, "max_row_blocks": v.max_row_blocks,
+        "covers_all": v.covers_all, "on_device": v.on_device,
+    }
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(None)
+
+
+def _tensors(q, k, v, o, lse, d_o=None, dq=None, dk=None, dv=None):
+    Bt, H, N, D = q.shape
+    assert q.stride(3) == 1 and k.stride(3) == 1 and v.stride(3) == 1 and o.stride(3) == 1
+    assert k.stride() == v.stride() and q.stride() == o.stride()
+    for g, ref in ((d_o, q), (dq, q), (dk, k), (dv, k)):
+        assert g is None or g.stride() == ref.stride()
+    assert lse.is_contiguous()
+    return Tensors(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(dq), _ptr(dk), _ptr(dv),
+                   Bt, H, N, D, q.stride(0), q.stride(1), q.stride(2), k.stride(0), k.stride(1), k.stride(2))
+
+
+def s2_attn_fwd(layout, q, k, v, o, lse, scale, stream=None):
+    t = _tensors(q, k, v, o, lse)
+    _check(lib().s2_attn_fwd(layout.handle, C.byref(t), scale, _stream_ptr(stream)), "s2_attn_fwd")
+
+
+def s2_attn_bwd_workspace_bytes(batch, heads, seqlen, head_dim):
+    return lib().s2_attn_bwd_workspace_bytes(batch, heads, seqlen, head_dim)
+
+
+def s2_attn_bwd(layout, q, k, v, o, lse, d_o, dq, dk, dv, scale, workspace, stream=None):
+    t = _tensors(q, k, v, o, lse, d_o, dq, dk, dv)
+    _check(lib().s2_attn_bwd(layout.handle, C.byref(t), scale, _ptr(workspace),
+                             workspace.numel() * workspace.element_size(), _stream_ptr(stream)),
+           "s2_attn_bwd")
+
+
+def s2_dense_causal_fwd(q, k, v, o, lse, scale, stream=None):
+    t = _tensors(q, k, v, o, lse)
+    _check(lib().s2_dense_causal_fwd(C.byref(t), scale, _stream_ptr(stream)), "s2_dense_causal_fwd")
+
+
+def s2_dense_causal_bwd(q, k, v, o, lse, d_o, dq, dk, dv, scale, workspace, stream=None):
+    t = _tensors(q, k, v, o, lse, d_o, dq, dk, dv)
+    _check(lib().s2_dense_causal_bwd(C.byref(t), scale, _ptr(workspace),
+                                     workspace.numel() * workspace.element_size(), _stream_ptr(stream)),
+           "s2_dense_causal_bwd")
+
+
+def s2_attn_decode_workspace_bytes(nseq, heads, head_dim, max_len, num_splits=0):
+    return lib().s2_attn_decode_workspace_bytes(nseq, heads, head_dim, max_len, num_splits)
+
+
+def s2_attn_decode_default_splits(nseq, heads, max_len):
+    return lib().s2_attn_decode_default_splits(nseq, heads, max_len)
+
+
+def s2_attn_decode(params, q, k_cache, v_cache, seq_lens, o, lse, scale, workspace, max_len,
+                   num_splits=0, stream=None):
+    nseq, H, D = q.shape
+    assert q.is_contiguous() and o.is_contiguous() and k_cache.stride() == v_cache.stride()
+    assert k_cache.stride(3) == 1
+    a = DecodeArgs(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seq_lens), _ptr(o), _ptr(lse),
+                   nseq, H, D, max_len, num_splits,
+                   k_cache.stride(0), k_cache.stride(1), k_cache.stride(2))
+    _check(lib().s2_attn_decode(C.byref(params), C.byref(a), scale, _ptr(workspace),
+                                workspace.numel() * workspace.element_size(), _stream_ptr(stream)),
+           "s2_attn_decode")

@@ -1,0 +1,343 @@
+// C ABI of libs2attn.so: argument validation, the layout handle's device copies, and dispatch to
+// the kernels.  See include/s2attn.h for the contract of every entry point.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "../../include/s2attn.h"
+#include "config.h"
+#include "kernels.h"
+#include "layout.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+inline bool hip_ok(hipError_t e) {
+  if (e == hipSuccess) return true;
+  g_last_hip_error = (int)e;
+  return false;
+}
+
+bool upload(const std::vector<int32_t>& host, int32_t** dev) {
+  *dev = nullptr;
+  const size_t bytes = (host.empty() ? 1 : host.size()) * sizeof(int32_t);
+  if (!hip_ok(hipMalloc(reinterpret_cast<void**>(dev), bytes))) return false;
+  if (host.empty()) return true;
+  return hip_ok(hipMemcpy(*dev, host.data(), host.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+}
+
+bool upload_tiles(s2::TileList& t) {
+  return upload(t.ptr, &t.d_ptr) && upload(t.ent, &t.d_ent) && upload(t.order, &t.d_order);
+}
+
+void free_tiles(s2::TileList& t) {
+  if (t.d_ptr) (void)hipFree(t.d_ptr);
+  if (t.d_ent) (void)hipFree(t.d_ent);
+  if (t.d_order) (void)hipFree(t.d_order);
+  t.d_ptr = t.d_ent = t.d_order = nullptr;
+}
+
+s2::DevTiles dev_tiles(const s2::TileList& t) {
+  s2::DevTiles d;
+  d.ptr = t.d_ptr;
+  d.ent = t.d_ent;
+  d.order = t.d_order;
+  d.tiles_per_head = t.tiles_per_head;
+  d.group = t.group;
+  return d;
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Shape / alignment checks shared by forward and backward.  `need_bwd` also checks the
+// gradient tensors.
+int check_tensors(const s2_tensors* t, bool need_bwd, float scale) {
+  if (!t) return S2_ERR_NULL;
+  if (!t->q || !t->k || !t->v || !t->o || !t->lse) return S2_ERR_NULL;
+  if (need_bwd && (!t->d_o || !t->dq || !t->dk || !t->dv)) return S2_ERR_NULL;
+  if (!(scale > 0.f) || !std::isfinite(scale)) return S2_ERR_BAD_PARAM;
+  if (t->batch < 1 || t->heads < 1 || t->seqlen < 1) return S2_ERR_SHAPE;
+  if (t->head_dim != 64 && t->head_dim != 128) return S2_ERR_SHAPE;
+  if ((int64_t)t->batch * t->heads * t->seqlen > (int64_t)1 << 40) return S2_ERR_SHAPE;
+  const int64_t strides[6] = {t->q_stride_b, t->q_stride_h, t->q_stride_t,
+                              t->kv_stride_b, t->kv_stride_h, t->kv_stride_t};
+  for (int64_t s : strides)
+    if (s < 0 || (s & 7) != 0) return S2_ERR_ALIGN;
+  if (t->q_stride_t < t->head_dim || t->kv_stride_t < t->head_dim) return S2_ERR_ALIGN;
+  const void* ptrs[9] = {t->q, t->k, t->v, t->o, t->lse, t->d_o, t->dq, t->dk, t->dv};
+  for (int i = 0; i < (need_bwd ? 9 : 5); ++i)
+    if (!aligned16(ptrs[i])) return S2_ERR_ALIGN;
+  return S2_OK;
+}
+
+s2::AttnParams make_params(const s2_tensors* t, float scale) {
+  s2::AttnParams p{};
+  p.q = static_cast<const uint16_t*>(t->q);
+  p.k = static_cast<const uint16_t*>(t->k);
+  p.v = static_cast<const uint16_t*>(t->v);
+  p.o = static_cast<uint16_t*>(t->o);
+  p.lse = t->lse;
+  p.d_o = static_cast<const uint16_t*>(t->d_o);
+  p.dq = static_cast<uint16_t*>(t->dq);
+  p.dk = static_cast<uint16_t*>(t->dk);
+  p.dv = static_cast<uint16_t*>(t->dv);
+  p.batch = t->batch;
+  p.heads = t->heads;
+  p.seqlen = t->seqlen;
+  p.head_dim = t->head_dim;
+  p.q_sb = t->q_stride_b;
+  p.q_sh = t->q_stride_h;
+  p.q_st = t->q_stride_t;
+  p.kv_sb = t->kv_stride_b;
+  p.kv_sh = t->kv_stride_h;
+  p.kv_st = t->kv_stride_t;
+  p.scale = scale;
+  p.scale_log2e = scale * 1.4426950408889634f;
+  return p;
+}
+
+int check_layout_fits(const s2_layout* L, const s2_tensors* t) {
+  if (!L) return S2_ERR_NULL;
+  if (t->heads != L->p.num_heads) return S2_ERR_SHAPE;
+  if ((int64_t)t->seqlen != (int64_t)L->p.num_blocks * L->p.block_size) return S2_ERR_SHAPE;
+  return S2_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int s2_layout_build(const s2_layout_params* params, s2_layout** out) {
+  if (!params || !out) return S2_ERR_NULL;
+  *out = nullptr;
+  s2_layout* L = new (std::nothrow) s2_layout();
+  if (!L) return S2_ERR_OVERFLOW;
+  int st;
+  try {
+    st = s2::build_host(*params, *L);
+    if (st == S2_OK) {
+      s2::build_tiles(*L, s2::kFwdBM / params->block_size, false, L->q_tiles);
+      s2::build_tiles(*L, s2::kBwdBN / params->block_size, true, L->kv_tiles);
+    }
+  } catch (const std::bad_alloc&) {
+    st = S2_ERR_OVERFLOW;
+  }
+  if (st != S2_OK) {
+    delete L;
+    return st;
+  }
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) == hipSuccess && ndev > 0) {
+    int dev = 0;
+    bool ok = hip_ok(hipGetDevice(&dev)) && upload_tiles(L->q_tiles) && upload_tiles(L->kv_tiles);
+    if (!ok) {
+      free_tiles(L->q_tiles);
+      free_tiles(L->kv_tiles);
+      delete L;
+      return S2_ERR_HIP;
+    }
+    L->device = dev;
+    L->on_device = true;
+  } else {
+    (void)hipGetLastError();  // no GPU: a host-only layout is still a valid result
+  }
+  *out = L;
+  return S2_OK;
+}
+
+int s2_layout_destroy(s2_layout* layout) {
+  if (!layout) return S2_ERR_NULL;
+  if (layout->on_device) {
+    free_tiles(layout->q_tiles);
+    free_tiles(layout->kv_tiles);
+  }
+  delete layout;
+  return S2_OK;
+}
+
+int s2_layout_get(const s2_layout* L, s2_layout_view* out) {
+  if (!L || !out) return S2_ERR_NULL;
+  out->row_ptr = L->row_ptr.data();
+  out->col_idx = L->col_idx.data();
+  out->col_ptr = L->col_ptr.data();
+  out->row_idx = L->row_idx.data();
+  out->nnz = L->nnz;
+  out->num_heads = L->p.num_heads;
+  out->num_blocks = L->p.num_blocks;
+  out->block_size = L->p.block_size;
+  out->max_row_blocks = L->max_row_blocks;
+  out->covers_all = L->covers_all;
+  out->on_device = L->on_device ? 1 : 0;
+  return S2_OK;
+}
+
+int s2_attn_fwd(const s2_layout* layout, const s2_tensors* t, float scale, void* stream) {
+  if (!layout) return S2_ERR_NULL;
+  int st = check_tensors(t, false, scale);
+  if (st != S2_OK) return st;
+  st = check_layout_fits(layout, t);
+  if (st != S2_OK) return st;
+  if (!layout->on_device) return S2_ERR_NO_DEVICE;
+  s2::AttnParams p = make_params(t, scale);
+  p.block_size = layout->p.block_size;
+  p.q_tiles = dev_tiles(layout->q_tiles);
+  p.kv_tiles = dev_tiles(layout->kv_tiles);
+  return hip_ok(s2::launch_fwd(p, false, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
+}
+
+size_t s2_attn_bwd_workspace_bytes(int32_t batch, int32_t heads, int32_t seqlen, int32_t head_dim) {
+  (void)head_dim;
+  if (batch < 1 || heads < 1 || seqlen < 1) return 0;
+  const size_t rows = (size_t)batch * heads * seqlen;
+  return ((rows * sizeof(float) + 255) / 256) * 256;  // delta = rowsum(dO * O)
+}
+
+int s2_attn_bwd(const s2_layout* layout, const s2_tensors* t, float scale, void* workspace,
+                size_t workspace_bytes, void* stream) {
+  if (!layout) return S2_ERR_NULL;
+  int st = check_tensors(t, true, scale);
+  if (st != S2_OK) return st;
+  st = check_layout_fits(layout, t);
+  if (st != S2_OK) return st;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 ||
+      workspace_bytes < s2_attn_bwd_workspace_bytes(t->batch, t->heads, t->seqlen, t->head_dim))
+    return S2_ERR_WORKSPACE;
+  if (!layout->on_device) return S2_ERR_NO_DEVICE;
+  s2::AttnParams p = make_params(t, scale);
+  p.delta = static_cast<float*>(workspace);
+  p.block_size = layout->p.block_size;
+  p.q_tiles = dev_tiles(layout->q_tiles);
+  p.kv_tiles = dev_tiles(layout->kv_tiles);
+  return hip_ok(s2::launch_bwd(p, false, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
+}
+
+static int dense_params(const s2_tensors* t, s2::AttnParams& p) {
+  if (t->seqlen % 128 != 0) return S2_ERR_SHAPE;
+  p.block_size = s2::kChunk;
+  p.q_tiles.tiles_per_head = t->seqlen / s2::kFwdBM;
+  p.q_tiles.group = s2::kFwdBM / s2::kChunk;
+  p.kv_tiles.tiles_per_head = t->seqlen / s2::kBwdBN;
+  p.kv_tiles.group = s2::kBwdBN / s2::kChunk;
+  return S2_OK;
+}
+
+int s2_dense_causal_fwd(const s2_tensors* t, float scale, void* stream) {
+  int st = check_tensors(t, false, scale);
+  if (st != S2_OK) return st;
+  s2::AttnParams p = make_params(t, scale);
+  st = dense_params(t, p);
+  if (st != S2_OK) return st;
+  return hip_ok(s2::launch_fwd(p, true, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
+}
+
+int s2_dense_causal_bwd(const s2_tensors* t, float scale, void* workspace, size_t workspace_bytes,
+                        void* stream) {
+  int st = check_tensors(t, true, scale);
+  if (st != S2_OK) return st;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 ||
+      workspace_bytes < s2_attn_bwd_workspace_bytes(t->batch, t->heads, t->seqlen, t->head_dim))
+    return S2_ERR_WORKSPACE;
+  s2::AttnParams p = make_params(t, scale);
+  st = dense_params(t, p);
+  if (st != S2_OK) return st;
+  p.delta = static_cast<float*>(workspace);
+  return hip_ok(s2::launch_bwd(p, true, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
+}
+
+int32_t s2_attn_decode_default_splits(int32_t nseq, int32_t heads, int32_t max_len) {
+  if (nseq < 1 || heads < 1 || max_len < 1) return 1;
+  // aim for a few workgroups per compute unit (256 CUs); never more splits than 1K-token pieces
+  const int64_t pairs = (int64_t)nseq * heads;
+  int64_t want = (4 * 256 + pairs - 1) / pairs;
+  const int64_t cap = (max_len + 1023) / 1024;
+  if (want > cap) want = cap;
+  if (want < 1) want = 1;
+  if (want > 64) want = 64;
+  return (int32_t)want;
+}
+
+size_t s2_attn_decode_workspace_bytes(int32_t nseq, int32_t heads, int32_t head_dim, int32_t max_len,
+                                      int32_t num_splits) {
+  if (nseq < 1 || heads < 1 || head_dim < 1) return 0;
+  if (num_splits <= 0) num_splits = s2_attn_decode_default_splits(nseq, heads, max_len);
+  const size_t items = (size_t)nseq * heads * num_splits;
+  return ((items * (head_dim + 2) * sizeof(float) + 255) / 256) * 256;
+}
+
+int s2_attn_decode(const s2_layout_params* lp, const s2_decode_args* a, float scale, void* workspace,
+                   size_t workspace_bytes, void* stream) {
+  if (!lp || !a) return S2_ERR_NULL;
+  if (!a->q || !a->k_cache || !a->v_cache || !a->seq_lens || !a->o) return S2_ERR_NULL;
+  if (!(scale > 0.f) || !std::isfinite(scale)) return S2_ERR_BAD_PARAM;
+  if (lp->block_size != 64 && lp->block_size != 128) return S2_ERR_BAD_PARAM;
+  if (lp->dense != 0 && lp->dense != 1) return S2_ERR_BAD_PARAM;
+  if (!lp->dense && (lp->local_blocks < 1 || lp->stride < 0 || lp->window_blocks < 0)) return S2_ERR_BAD_PARAM;
+  if (lp->head_index_base < 0) return S2_ERR_BAD_PARAM;
+  if (a->nseq < 1 || a->heads < 1 || a->max_len < 1) return S2_ERR_SHAPE;
+  if (a->heads != lp->num_heads) return S2_ERR_SHAPE;
+  if (a->head_dim != 64 && a->head_dim != 128) return S2_ERR_SHAPE;
+  if (a->num_splits < 0 || a->num_splits > 64) return S2_ERR_BAD_PARAM;
+  const int64_t strides[3] = {a->kv_stride_seq, a->kv_stride_head, a->kv_stride_tok};
+  for (int64_t s : strides)
+    if (s < 0 || (s & 7) != 0) return S2_ERR_ALIGN;
+  if (a->kv_stride_tok < a->head_dim) return S2_ERR_ALIGN;
+  if (!aligned16(a->q) || !aligned16(a->k_cache) || !aligned16(a->v_cache) || !aligned16(a->o) ||
+      (reinterpret_cast<uintptr_t>(a->seq_lens) & 3u) != 0)
+    return S2_ERR_ALIGN;
+  const int splits = a->num_splits > 0 ? a->num_splits
+                                       : s2_attn_decode_default_splits(a->nseq, a->heads, a->max_len);
+  const size_t need = s2_attn_decode_workspace_bytes(a->nseq, a->heads, a->head_dim, a->max_len, splits);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || workspace_bytes < need)
+    return S2_ERR_WORKSPACE;
+
+  s2::DecodeParams p{};
+  p.q = static_cast<const uint16_t*>(a->q);
+  p.k_cache = static_cast<const uint16_t*>(a->k_cache);
+  p.v_cache = static_cast<const uint16_t*>(a->v_cache);
+  p.seq_lens = a->seq_lens;
+  p.o = static_cast<uint16_t*>(a->o);
+  p.lse = a->lse;
+  const size_t items = (size_t)a->nseq * a->heads * splits;
+  p.part_acc = static_cast<float*>(workspace);
+  p.part_ml = p.part_acc + items * a->head_dim;
+  p.nseq = a->nseq;
+  p.heads = a->heads;
+  p.head_dim = a->head_dim;
+  p.max_len = a->max_len;
+  p.num_splits = splits;
+  p.kv_ss = a->kv_stride_seq;
+  p.kv_sh = a->kv_stride_head;
+  p.kv_st = a->kv_stride_tok;
+  p.scale = scale;
+  p.scale_log2e = scale * 1.4426950408889634f;
+  p.block_size = lp->block_size;
+  p.local_blocks = lp->local_blocks;
+  p.stride = lp->stride;
+  p.window_blocks = lp->window_blocks;
+  p.dense = lp->dense;
+  p.head_index_base = lp->head_index_base;
+  return hip_ok(s2::launch_decode(p, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
+}
+
+const char* s2_status_string(int status) {
+  switch (status) {
+    case S2_OK: return "ok";
+    case S2_ERR_NULL: return "a required pointer is NULL";
+    case S2_ERR_BAD_PARAM: return "parameter out of range";
+    case S2_ERR_SHAPE: return "tensor shape does not fit";
+    case S2_ERR_ALIGN: return "pointer or stride not aligned";
+    case S2_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case S2_ERR_HIP: return "HIP runtime error";
+    case S2_ERR_NO_DEVICE: return "layout has no device copy";
+    case S2_ERR_OVERFLOW: return "size overflow or out of memory";
+    default: return "unknown status";
+  }
+}
+
+int s2_last_hip_error(void) { return g_last_hip_error; }
+int s2_version(void) { return 100; }
+
+}  // extern "C"

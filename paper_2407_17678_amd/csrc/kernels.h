@@ -1,0 +1,59 @@
+// Internal: parameter blocks and launch entry points of the HIP kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace s2 {
+
+// Merged tile list on the device (see TileList in layout.h).
+struct DevTiles {
+  const int32_t* ptr = nullptr;
+  const int32_t* ent = nullptr;
+  const int32_t* order = nullptr;
+  int tiles_per_head = 0;
+  int group = 0;
+};
+
+struct AttnParams {
+  const uint16_t* q;
+  const uint16_t* k;
+  const uint16_t* v;
+  uint16_t* o;
+  float* lse;
+  const uint16_t* d_o;
+  uint16_t* dq;
+  uint16_t* dk;
+  uint16_t* dv;
+  float* delta;  // workspace: rowsum(dO * O), [batch, heads, seqlen]
+  int batch, heads, seqlen, head_dim;
+  int64_t q_sb, q_sh, q_st;
+  int64_t kv_sb, kv_sh, kv_st;
+  float scale;        // softmax scale
+  float scale_log2e;  // scale * log2(e)
+  int block_size;     // S (sparse path); 64 on the dense path
+  DevTiles q_tiles;   // row tiles -> KV blocks
+  DevTiles kv_tiles;  // column tiles -> Q blocks
+};
+
+struct DecodeParams {
+  const uint16_t* q;
+  const uint16_t* k_cache;
+  const uint16_t* v_cache;
+  const int32_t* seq_lens;
+  uint16_t* o;
+  float* lse;
+  float* part_acc;  // [nseq*heads*splits, head_dim]
+  float* part_ml;   // [nseq*heads*splits, 2]  (max, sum)
+  int nseq, heads, head_dim, max_len, num_splits;
+  int64_t kv_ss, kv_sh, kv_st;
+  float scale, scale_log2e;
+  int block_size, local_blocks, stride, window_blocks, dense, head_index_base;
+};
+
+// Each returns the hipError_t of the launch (hipGetLastError after the launch).
+hipError_t launch_fwd(const AttnParams& p, bool dense, hipStream_t stream);
+hipError_t launch_bwd(const AttnParams& p, bool dense, hipStream_t stream);
+hipError_t launch_decode(const DecodeParams& p, hipStream_t stream);
+
+}  // namespace s2

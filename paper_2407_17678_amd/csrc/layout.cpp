@@ -1,0 +1,168 @@
+// Host-side layout builder: the per-head block mask of section 4.2 written out in closed form
+// as compressed lists (section 3.2 stores the mask in compressed-sparse-row form), plus the
+// merged tile lists the kernels iterate over.  Integer work only; no HIP calls in this file.
+#include "layout.h"
+
+#include <algorithm>
+#include <limits>
+#include <numeric>
+
+namespace s2 {
+
+namespace {
+
+inline int head_offset(const s2_layout_params& p, int h) {
+  return p.stride > 0 ? (p.head_index_base + h) % p.stride : 0;
+}
+
+// Kept columns of block row i, ascending: the stripe columns o, o+s, ... that lie at least B_l
+// rows back (and inside the window), then the local run ending at the diagonal.
+template <class F>
+inline void for_row(const s2_layout_params& p, int o, int i, F&& emit) {
+  if (p.dense) {
+    for (int j = 0; j <= i; ++j) emit(j);
+    return;
+  }
+  const int local_lo = std::max(0, i - p.local_blocks + 1);
+  if (p.stride > 0) {
+    int lo = 0;  // smallest admissible column
+    if (p.window_blocks > 0) lo = std::max(0, i - p.window_blocks + 1);
+    // first stripe column >= lo
+    int j = o;
+    if (lo > o) j = o + ((lo - o + p.stride - 1) / p.stride) * p.stride;
+    for (; j < local_lo; j += p.stride) emit(j);
+  }
+  for (int j = local_lo; j <= i; ++j) emit(j);
+}
+
+// Rows keeping block column j, ascending: the local run starting at the diagonal, then (when j
+// lies on one of the head's stripes) every later row inside the window.
+template <class F>
+inline void for_col(const s2_layout_params& p, int o, int j, F&& emit) {
+  const int B = p.num_blocks;
+  if (p.dense) {
+    for (int i = j; i < B; ++i) emit(i);
+    return;
+  }
+  const int local_hi = std::min(B - 1, j + p.local_blocks - 1);
+  for (int i = j; i <= local_hi; ++i) emit(i);
+  if (p.stride > 0 && j >= o && (j - o) % p.stride == 0) {
+    int hi = B - 1;
+    if (p.window_blocks > 0) hi = std::min(hi, j + p.window_blocks - 1);
+    for (int i = local_hi + 1; i <= hi; ++i) emit(i);
+  }
+}
+
+}  // namespace
+
+int build_host(const s2_layout_params& p, s2_layout& L) {
+  if (p.num_heads < 1 || p.num_blocks < 1 || p.head_index_base < 0) return S2_ERR_BAD_PARAM;
+  if (p.block_size != 64 && p.block_size != 128) return S2_ERR_BAD_PARAM;
+  if (!p.dense && (p.local_blocks < 1 || p.stride < 0 || p.window_blocks < 0)) return S2_ERR_BAD_PARAM;
+  if (p.dense != 0 && p.dense != 1) return S2_ERR_BAD_PARAM;
+  const int H = p.num_heads, B = p.num_blocks;
+  if ((int64_t)H * B + 1 > std::numeric_limits<int32_t>::max()) return S2_ERR_OVERFLOW;
+  if ((int64_t)B * p.block_size > std::numeric_limits<int32_t>::max()) return S2_ERR_OVERFLOW;
+
+  L.p = p;
+  // pass 1: count
+  int64_t nnz = 0;
+  int max_row = 0;
+  L.row_ptr.assign((size_t)H * B + 1, 0);
+  for (int h = 0; h < H; ++h) {
+    const int o = head_offset(p, h);
+    for (int i = 0; i < B; ++i) {
+      int c = 0;
+      for_row(p, o, i, [&](int) { ++c; });
+      nnz += c;
+      if (nnz > std::numeric_limits<int32_t>::max()) return S2_ERR_OVERFLOW;
+      max_row = std::max(max_row, c);
+      L.row_ptr[(size_t)h * B + i + 1] = (int32_t)nnz;
+    }
+  }
+  L.nnz = nnz;
+  L.max_row_blocks = max_row;
+  // pass 2: fill rows
+  L.col_idx.resize((size_t)nnz);
+  for (int h = 0; h < H; ++h) {
+    const int o = head_offset(p, h);
+    for (int i = 0; i < B; ++i) {
+      int32_t* dst = L.col_idx.data() + L.row_ptr[(size_t)h * B + i];
+      for_row(p, o, i, [&](int j) { *dst++ = j; });
+    }
+  }
+  // transpose, also in closed form
+  L.col_ptr.assign((size_t)H * B + 1, 0);
+  L.row_idx.resize((size_t)nnz);
+  int64_t n = 0;
+  for (int h = 0; h < H; ++h) {
+    const int o = head_offset(p, h);
+    for (int j = 0; j < B; ++j) {
+      for_col(p, o, j, [&](int i) { L.row_idx[(size_t)n++] = i; });
+      L.col_ptr[(size_t)h * B + j + 1] = (int32_t)n;
+    }
+  }
+  if (n != nnz) return S2_ERR_BAD_PARAM;  // the two closed forms disagree: a bug, never silent
+
+  // union over heads covers every causal block?  Count distinct (i,j) kept by any head.
+  {
+    std::vector<uint8_t> seen((size_t)B);
+    bool all = true;
+    for (int i = 0; i < B && all; ++i) {
+      std::fill(seen.begin(), seen.begin() + i + 1, 0);
+      for (int h = 0; h < H; ++h) {
+        const int32_t* c = L.col_idx.data() + L.row_ptr[(size_t)h * B + i];
+        const int32_t* e = L.col_idx.data() + L.row_ptr[(size_t)h * B + i + 1];
+        for (; c != e; ++c) seen[*c] = 1;
+      }
+      for (int j = 0; j <= i; ++j)
+        if (!seen[j]) { all = false; break; }
+    }
+    L.covers_all = all ? 1 : 0;
+  }
+  return S2_OK;
+}
+
+void build_tiles(const s2_layout& L, int group, bool transpose, TileList& out) {
+  const int H = L.p.num_heads, B = L.p.num_blocks;
+  const std::vector<int32_t>& ptr = transpose ? L.col_ptr : L.row_ptr;
+  const std::vector<int32_t>& idx = transpose ? L.row_idx : L.col_idx;
+  const int T = (B + group - 1) / group;
+  out.group = group;
+  out.tiles_per_head = T;
+  out.ptr.assign((size_t)H * T + 1, 0);
+  out.ent.clear();
+  out.order.resize((size_t)H * T);
+  out.max_len = 0;
+  std::vector<int> cur(group), end(group);
+  for (int h = 0; h < H; ++h) {
+    for (int t = 0; t < T; ++t) {
+      const int members = std::min(group, B - t * group);
+      for (int r = 0; r < members; ++r) {
+        cur[r] = ptr[(size_t)h * B + t * group + r];
+        end[r] = ptr[(size_t)h * B + t * group + r + 1];
+      }
+      const size_t start = out.ent.size();
+      for (;;) {  // k-way merge of ascending lists
+        int best = std::numeric_limits<int>::max();
+        for (int r = 0; r < members; ++r)
+          if (cur[r] < end[r]) best = std::min(best, (int)idx[cur[r]]);
+        if (best == std::numeric_limits<int>::max()) break;
+        int bits = 0;
+        for (int r = 0; r < members; ++r)
+          if (cur[r] < end[r] && idx[cur[r]] == best) { bits |= 1 << r; ++cur[r]; }
+        out.ent.push_back((int32_t)((best << 8) | bits));
+      }
+      const int len = (int)(out.ent.size() - start);
+      out.max_len = std::max(out.max_len, len);
+      out.ptr[(size_t)h * T + t + 1] = (int32_t)out.ent.size();
+    }
+    // heaviest tiles first inside the head, so the tail of a launch is made of short tiles
+    int32_t* ord = out.order.data() + (size_t)h * T;
+    std::iota(ord, ord + T, 0);
+    const int32_t* hp = out.ptr.data() + (size_t)h * T;
+    std::stable_sort(ord, ord + T, [&](int a, int b) { return hp[a + 1] - hp[a] > hp[b + 1] - hp[b]; });
+  }
+}
+
+}  // namespace s2

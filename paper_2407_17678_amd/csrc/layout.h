@@ -1,0 +1,45 @@
+// Internal: host-side layout handle shared by the layout builder and the launch code.
+#pragma once
+#include <cstdint>
+#include <vector>
+
+#include "../../include/s2attn.h"
+
+namespace s2 {
+
+// Merged tile list: consecutive groups of `group` block rows (or block columns) share one list
+// of partner blocks; each entry packs (partner_index << 8) | membership_bits, bit r set when
+// member r of the group keeps that partner.  This is the Merge-Q idea of section 3.2 (one
+// large tile serves several fine-grained mask rows) and its mirror image for key tiles.
+struct TileList {
+  int group = 0;                 // members per tile (1..8)
+  int tiles_per_head = 0;        // ceil(B / group)
+  std::vector<int32_t> ptr;      // [H*tiles_per_head + 1]
+  std::vector<int32_t> ent;      // packed entries, partner ascending inside a tile
+  std::vector<int32_t> order;    // [H*tiles_per_head]: per head, tile ids by descending length
+  int32_t* d_ptr = nullptr;      // device copies (owned by the layout)
+  int32_t* d_ent = nullptr;
+  int32_t* d_order = nullptr;
+  int max_len = 0;
+};
+
+}  // namespace s2
+
+struct s2_layout {
+  s2_layout_params p{};
+  std::vector<int32_t> row_ptr, col_idx, col_ptr, row_idx;
+  int64_t nnz = 0;
+  int max_row_blocks = 0;
+  int covers_all = 0;
+  bool on_device = false;
+  int device = -1;
+  s2::TileList q_tiles;   // row groups  -> kept KV blocks   (forward, dQ pass)
+  s2::TileList kv_tiles;  // column groups -> attending Q blocks (dK/dV pass)
+};
+
+namespace s2 {
+// Host-only construction (no HIP calls).  Returns an S2_* status.
+int build_host(const s2_layout_params& p, s2_layout& L);
+// Merge `group` consecutive rows (transpose=false) or columns (transpose=true).
+void build_tiles(const s2_layout& L, int group, bool transpose, TileList& out);
+}  // namespace s2

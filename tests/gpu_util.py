@@ -1,0 +1,49 @@
+"""Helpers shared by the GPU parity tests: bf16 bit patterns <-> torch tensors, oracle calls."""
+
+import numpy as np
+import torch
+
+from oracle import s2_oracle as orc
+from paper_2407_17678_amd import binding as B
+from paper_2407_17678_amd import synth
+
+
+def to_dev(bits):
+    """uint16 bf16 bit patterns (numpy) -> torch.bfloat16 tensor on cuda:0 with the same bits."""
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
+    return t.view(torch.bfloat16)
+
+
+def to_f64(t):
+    """bf16 / fp32 device tensor -> float64 numpy (exact)."""
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def bits_f64(bits):
+    return synth.bf16_bits_to_f32(bits).astype(np.float64)
+
+
+def rel_l2(got, want):
+    return float(np.linalg.norm((got - want).ravel()) / max(np.linalg.norm(want.ravel()), 1e-300))
+
+
+def run_fwd(w, qb, kb, vb, dense=False):
+    """Runs the library forward on bf16 bit patterns; returns (o, lse, layout, device tensors)."""
+    q, k, v = to_dev(qb), to_dev(kb), to_dev(vb)
+    Bt, H, N, D = q.shape
+    o = torch.empty_like(q)
+    lse = torch.empty((Bt, H, N), dtype=torch.float32, device="cuda")
+    lay = None
+    if dense:
+        B.s2_dense_causal_fwd(q, k, v, o, lse, w.scale)
+    else:
+        lay = B.s2_layout_build(B.layout_params(H, N // w.block_size, w.block_size, w.local_blocks,
+                                                w.stride, 0, w.window_blocks, 0))
+        B.s2_attn_fwd(lay, q, k, v, o, lse, w.scale)
+    torch.cuda.synchronize()
+    return o, lse, lay, (q, k, v)
+
+
+def oracle_mask(w, H, N, dense=False):
+    return orc.block_mask(H, N // w.block_size, w.local_blocks, w.stride,
+                          window_blocks=w.window_blocks, dense=dense)

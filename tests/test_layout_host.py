@@ -1,0 +1,173 @@
+"""CPU tests of the library's host side: symbols, the closed-form layout builder (bit-exact
+against the oracle's scan of the predicate), and every argument-error path.  No kernel runs."""
+
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import s2_oracle as orc
+from paper_2407_17678_amd import binding as B
+from paper_2407_17678_amd.synth import WORKLOADS
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "s2attn.h")).read()
+    declared = set(re.findall(r"\b(s2_[a-z_0-9]+)\s*\(", header))
+    assert declared, "no declarations found"
+    lib = B.lib()
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+    assert declared == set(B.EXPORTS)
+    assert lib.s2_version() >= 100
+    assert lib.s2_status_string(0) == b"ok"
+    for code in range(-8, 0):
+        assert lib.s2_status_string(code) not in (b"ok", b"unknown status")
+
+
+def _compare(H, Bk, S, B_l, s, base=0, win=0, dense=0):
+    lay = B.s2_layout_build(B.layout_params(H, Bk, S, B_l, s, base, win, dense))
+    got = B.s2_layout_get(lay)
+    M = orc.block_mask(H, Bk, B_l, s, head_index_base=base, window_blocks=win, dense=bool(dense))
+    row_ptr, col_idx, col_ptr, row_idx = orc.compressed_layout(M)
+    assert got["nnz"] == int(M.sum())
+    for name, want in (("row_ptr", row_ptr), ("col_idx", col_idx), ("col_ptr", col_ptr),
+                       ("row_idx", row_idx)):
+        assert got[name].dtype == np.int32
+        assert np.array_equal(got[name], want), name
+    assert got["covers_all"] == int(orc.covers_all(M))
+    assert got["max_row_blocks"] == int(M.sum(axis=2).max())
+    B.s2_layout_destroy(lay)
+    return got
+
+
+@pytest.mark.parametrize("name", ["tiny", "1p3b_8k", "7b_32k", "7b_128k"])
+def test_layout_bit_exact_at_workloads(name):
+    w = WORKLOADS[name]
+    got = _compare(w.heads, w.num_blocks, w.block_size, w.local_blocks, w.stride)
+    assert got["nnz"] == {"tiny": 81, "1p3b_8k": 23596, "7b_32k": 504816, "7b_128k": 777884}[name]
+    assert got["covers_all"] == 1
+
+
+def test_layout_bit_exact_random_parameters():
+    rng = np.random.default_rng(11)
+    for _ in range(120):
+        H = int(rng.integers(1, 10))
+        Bk = int(rng.integers(1, 70))
+        S = int(rng.choice([64, 128]))
+        B_l = int(rng.integers(1, 9))
+        s = int(rng.integers(0, 12))
+        base = int(rng.integers(0, 20))
+        win = int(rng.choice([0, 0, int(rng.integers(1, 70))]))
+        dense = int(rng.random() < 0.1)
+        _compare(H, Bk, S, B_l, s, base, win, dense)
+
+
+def test_layout_variants():
+    _compare(16, 128, 64, 1, 15)        # L1V15
+    _compare(16, 128, 64, 9, 0)         # sliding window only
+    _compare(16, 128, 64, 2, 18)        # stride above head count: union incomplete
+    assert _compare(16, 128, 64, 2, 18)["covers_all"] == 0
+    _compare(4, 33, 128, 200, 3)        # B_l >= B is dense
+    _compare(8, 64, 64, 4, 8, base=8)   # second tensor-parallel shard of 16 heads
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(num_heads=0), -2), (dict(num_blocks=0), -2), (dict(block_size=32), -2),
+    (dict(local_blocks=0), -2), (dict(stride=-1), -2), (dict(window_blocks=-1), -2),
+    (dict(head_index_base=-1), -2), (dict(dense=2), -2),
+])
+def test_layout_bad_params(kw, code):
+    args = dict(num_heads=2, num_blocks=4, block_size=64, local_blocks=1, stride=2, head_index_base=0,
+                window_blocks=0, dense=0)
+    args.update(kw)
+    with pytest.raises(B.S2Error) as e:
+        B.s2_layout_build(B.layout_params(**args))
+    assert e.value.status == code
+
+
+def test_null_and_overflow_paths():
+    lib = B.lib()
+    out = C.c_void_p()
+    assert lib.s2_layout_build(None, C.byref(out)) == -1
+    p = B.layout_params(1, 1, 64, 1, 0)
+    assert lib.s2_layout_build(C.byref(p), None) == -1
+    assert lib.s2_layout_destroy(None) == -1
+    assert lib.s2_layout_get(None, None) == -1
+    # dense layout whose block count would overflow int32
+    big = B.layout_params(64, 70000, 64, 1, 0, dense=1)
+    assert lib.s2_layout_build(C.byref(big), C.byref(out)) == -8
+
+
+def _tensors(**kw):
+    base = dict(q=256, k=256, v=256, o=256, lse=256, d_o=256, dq=256, dk=256, dv=256, batch=1, heads=2,
+                seqlen=256, head_dim=128, q_stride_b=2 * 256 * 128, q_stride_h=256 * 128, q_stride_t=128,
+                kv_stride_b=2 * 256 * 128, kv_stride_h=256 * 128, kv_stride_t=128)
+    base.update(kw)
+    return B.Tensors(**base)
+
+
+def test_attention_argument_errors_without_device():
+    """Validation happens before any launch, so these run (and fail cleanly) with no GPU.
+    Pointers are fake non-null addresses that are never dereferenced on these paths."""
+    lib = B.lib()
+    lay = B.s2_layout_build(B.layout_params(2, 4, 64, 1, 2))
+    h = lay.handle
+    call = lambda t, scale=0.1: lib.s2_attn_fwd(h, C.byref(t), scale, None)
+    assert lib.s2_attn_fwd(None, C.byref(_tensors()), 0.1, None) == -1
+    assert lib.s2_attn_fwd(h, None, 0.1, None) == -1
+    assert call(_tensors(q=None)) == -1
+    assert call(_tensors(), scale=0.0) == -2
+    assert call(_tensors(), scale=float("nan")) == -2
+    assert call(_tensors(head_dim=96)) == -3
+    assert call(_tensors(heads=3)) == -3
+    assert call(_tensors(seqlen=192)) == -3
+    assert call(_tensors(q=264)) == -4
+    assert call(_tensors(q_stride_t=132)) == -4
+    assert call(_tensors(kv_stride_t=64)) == -4
+    ws = 1 << 20
+    bwd = lambda t, wptr=256, wbytes=ws: lib.s2_attn_bwd(h, C.byref(t), 0.1, wptr, wbytes, None)
+    assert bwd(_tensors(dq=None)) == -1
+    assert bwd(_tensors(), wptr=None) == -5
+    assert bwd(_tensors(), wbytes=16) == -5
+    assert bwd(_tensors(), wptr=264) == -5
+    need = lib.s2_attn_bwd_workspace_bytes(1, 2, 256, 128)
+    assert need >= 1 * 2 * 256 * 4 and need % 256 == 0
+    assert lib.s2_dense_causal_fwd(C.byref(_tensors(seqlen=192)), 0.1, None) == -3
+    assert lib.s2_dense_causal_fwd(None, 0.1, None) == -1
+    import torch
+    if not torch.cuda.is_available():
+        # a host-only layout refuses to launch
+        assert B.s2_layout_get(lay)["on_device"] == 0
+        assert call(_tensors()) == -7
+
+
+def test_decode_argument_errors():
+    lib = B.lib()
+    p = B.layout_params(2, 1, 64, 2, 4)
+    def args(**kw):
+        base = dict(q=256, k_cache=256, v_cache=256, seq_lens=256, o=256, lse=None, nseq=3, heads=2,
+                    head_dim=128, max_len=1000, num_splits=2, kv_stride_seq=2 * 1000 * 128,
+                    kv_stride_head=1000 * 128, kv_stride_tok=128)
+        base.update(kw)
+        return B.DecodeArgs(**base)
+    call = lambda a, scale=0.1, ws=256, wb=1 << 20, pp=p: lib.s2_attn_decode(
+        C.byref(pp), C.byref(a), scale, ws, wb, None)
+    assert lib.s2_attn_decode(None, C.byref(args()), 0.1, 256, 1 << 20, None) == -1
+    assert call(args(q=None)) == -1
+    assert call(args(), scale=-1.0) == -2
+    assert call(args(heads=4)) == -3
+    assert call(args(head_dim=32)) == -3
+    assert call(args(num_splits=100)) == -2
+    assert call(args(kv_stride_tok=100)) == -4
+    assert call(args(k_cache=260)) == -4
+    assert call(args(), ws=None) == -5
+    assert call(args(), wb=8) == -5
+    assert call(args(), pp=B.layout_params(2, 1, 64, 0, 4)) == -2
+    need = lib.s2_attn_decode_workspace_bytes(3, 2, 128, 1000, 2)
+    assert need >= 3 * 2 * 2 * 130 * 4
+    assert 1 <= lib.s2_attn_decode_default_splits(64, 32, 32768) <= 64
