@@ -30,14 +30,16 @@ bool upload(const std::vector<int32_t>& host, int32_t** dev) {
 }
 
 bool upload_tiles(s2::TileList& t) {
-  return upload(t.ptr, &t.d_ptr) && upload(t.ent, &t.d_ent) && upload(t.order, &t.d_order);
+  return upload(t.ptr, &t.d_ptr) && upload(t.ent, &t.d_ent) && upload(t.order, &t.d_order) &&
+         upload(t.members, &t.d_members);
 }
 
 void free_tiles(s2::TileList& t) {
   if (t.d_ptr) (void)hipFree(t.d_ptr);
   if (t.d_ent) (void)hipFree(t.d_ent);
   if (t.d_order) (void)hipFree(t.d_order);
-  t.d_ptr = t.d_ent = t.d_order = nullptr;
+  if (t.d_members) (void)hipFree(t.d_members);
+  t.d_ptr = t.d_ent = t.d_order = t.d_members = nullptr;
 }
 
 s2::DevTiles dev_tiles(const s2::TileList& t) {
@@ -45,6 +47,7 @@ s2::DevTiles dev_tiles(const s2::TileList& t) {
   d.ptr = t.d_ptr;
   d.ent = t.d_ent;
   d.order = t.d_order;
+  d.members = t.d_members;
   d.tiles_per_head = t.tiles_per_head;
   d.group = t.group;
   return d;

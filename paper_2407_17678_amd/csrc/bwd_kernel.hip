@@ -1,5 +1,440 @@
-// placeholder until the backward kernels land
+// Backward kernels: gradients of block-sparse causal attention (the backward pass that goes with
+// the forward of section 3.2; the paper names it as the less optimised half of its kernels).
+//
+// Three launches, no atomics, bitwise reproducible:
+//   delta  : delta[t] = sum_d dO[t][d] * O[t][d]
+//   dq     : row-stationary.  A workgroup owns 128 query rows and walks the merged list of KV
+//            blocks its mask rows keep (as the forward does), recomputing P and forming
+//            dS = P * (dP - delta), dQ += scale * dS K.
+//   dkdv   : column-stationary.  A workgroup owns 128 keys - one or two mask columns, paired by
+//            the layout builder so that both are attended by nearly the same query blocks - and
+//            walks the query blocks that keep them: dV += P^T dO, dK += scale * dS^T Q.
+//
+// Both main kernels keep the stationary operand's MFMA fragments in registers with the lane
+// owning one stationary row, so the recomputed score tile lands in the C layout with the
+// streamed index in registers; it is then fed back as the B operand of the next contraction
+// without leaving the lane (see device_util.h).  The streamed 64-row chunk is staged through
+// LDS twice: row-major (k = feature) and transposed (k = token).
+#include <hip/hip_runtime.h>
+
+#include "config.h"
+#include "device_util.h"
 #include "kernels.h"
+
 namespace s2 {
-hipError_t launch_bwd(const AttnParams&, bool, hipStream_t) { return hipErrorNotSupported; }
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+// ------------------------------------------------------------------------------------ delta
+
+template <int D>
+__global__ __launch_bounds__(256) void delta_kernel(const AttnParams p) {
+  constexpr int LPR = D / 8;          // lanes per row
+  constexpr int RPB = 256 / LPR;      // rows per block
+  const int tid = threadIdx.x;
+  const int64_t row = (int64_t)blockIdx.x * RPB + tid / LPR;
+  const int c = tid % LPR;
+  const int64_t rows_total = (int64_t)p.batch * p.heads * p.seqlen;
+  float acc = 0.f;
+  if (row < rows_total) {
+    const int64_t bh = row / p.seqlen;
+    const int t = (int)(row - bh * p.seqlen);
+    const int b = (int)(bh / p.heads), h = (int)(bh - (int64_t)b * p.heads);
+    const int64_t off = b * p.q_sb + h * p.q_sh + (int64_t)t * p.q_st + 8 * c;
+    const bf16x8 o = *reinterpret_cast<const bf16x8*>(p.o + off);
+    const bf16x8 g = *reinterpret_cast<const bf16x8*>(p.d_o + off);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc += (float)o[e] * (float)g[e];
+  }
+#pragma unroll
+  for (int m = LPR / 2; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
+  if (c == 0 && row < rows_total) p.delta[row] = acc;
 }
+
+// ------------------------------------------------------------------------------------ dq
+
+template <int D>
+struct DqSmem {
+  uint16_t k[RowTile<D>::kElems];
+  uint16_t v[RowTile<D>::kElems];
+  uint16_t kt[TransposedTile<D>::kElems];
+};
+
+template <int D, bool DENSE>
+__global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  DqSmem<D>& sm = *reinterpret_cast<DqSmem<D>*>(smem_raw);
+
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+  const int T = p.q_tiles.tiles_per_head;
+  int bh, rank;
+  if (!map_workgroup(blockIdx.x, p.batch * p.heads, T, bh, rank)) return;
+  const int b = bh / p.heads, h = bh - b * p.heads;
+  const int tile = DENSE ? (T - 1 - rank) : p.q_tiles.order[h * T + rank];
+  const int S = DENSE ? kChunk : p.block_size;
+  const int cpb = S / kChunk;
+  const int N = p.seqlen;
+  const int qw0 = tile * kBwdBM + wave * 32;
+  const bool wave_active = qw0 < N;
+  const int my_member = (qw0 / S) - tile * (kBwdBM / S);
+
+  const int64_t q_off = b * p.q_sb + h * p.q_sh;
+  const int64_t kv_off = b * p.kv_sb + h * p.kv_sh;
+  const uint16_t* kb = p.k + kv_off;
+  const uint16_t* vb = p.v + kv_off;
+
+  bf16x8 qf[D / 16], gf[D / 16];  // Q^T and dO^T fragments (B operands), lane = query
+  float lse_l = 0.f, delta_l = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < D / 16; ++kk) {
+    if (wave_active) {
+      const int64_t o = q_off + (int64_t)(qw0 + l32) * p.q_st + 16 * kk + 8 * half;
+      qf[kk] = *reinterpret_cast<const bf16x8*>(p.q + o);
+      gf[kk] = *reinterpret_cast<const bf16x8*>(p.d_o + o);
+    } else {
+      qf[kk] = bf16x8{};
+      gf[kk] = bf16x8{};
+    }
+  }
+  if (wave_active) {
+    const int64_t r = ((int64_t)b * p.heads + h) * N + qw0 + l32;
+    lse_l = p.lse[r] * kLog2e;
+    delta_l = p.delta[r];
+  }
+
+  int ent_lo = 0, n_ent;
+  if (DENSE) {
+    n_ent = min(N, (tile + 1) * kBwdBM) / kChunk;
+  } else {
+    ent_lo = p.q_tiles.ptr[h * T + tile];
+    n_ent = p.q_tiles.ptr[h * T + tile + 1] - ent_lo;
+  }
+  const int total = n_ent * cpb;
+  auto chunk_of = [&](int it, int& kv0, bool& keep) {
+    if (DENSE) {
+      kv0 = it * kChunk;
+      keep = true;
+    } else {
+      const int e = p.q_tiles.ent[ent_lo + it / cpb];
+      kv0 = (e >> 8) * S + (it % cpb) * kChunk;
+      keep = (e >> my_member) & 1;
+    }
+  };
+
+  f32x16 acc[D / 32];
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt) acc[dt] = f32x16{};
+  const float c = p.scale_log2e;
+
+  u32x4 kreg[4];
+  u32x4 vreg[RowTile<D>::kPerThread];
+  if (total > 0) {
+    int kv0;
+    bool keep;
+    chunk_of(0, kv0, keep);
+    TransposedTile<D>::load(kreg, kb + (int64_t)kv0 * p.kv_st, p.kv_st, tid);
+    RowTile<D>::load(vreg, vb + (int64_t)kv0 * p.kv_st, p.kv_st, tid);
+    RowTile<D>::store_quad(kreg, sm.k, tid);
+    TransposedTile<D>::store(kreg, sm.kt, tid);
+    RowTile<D>::store(vreg, sm.v, tid);
+  }
+  __syncthreads();
+
+  for (int it = 0; it < total; ++it) {
+    int kv0;
+    bool keep;
+    chunk_of(it, kv0, keep);
+    if (it + 1 < total) {
+      int kv1;
+      bool keep1;
+      chunk_of(it + 1, kv1, keep1);
+      TransposedTile<D>::load(kreg, kb + (int64_t)kv1 * p.kv_st, p.kv_st, tid);
+      RowTile<D>::load(vreg, vb + (int64_t)kv1 * p.kv_st, p.kv_st, tid);
+    }
+
+    if (wave_active && keep && kv0 <= qw0 + 31) {
+      const int qpos = qw0 + l32;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+        const int kbase = kv0 + 32 * kt;
+        if (kbase > qw0 + 31) continue;  // every key of this half-chunk lies after my queries
+        f32x16 s = f32x16{}, dp = f32x16{};
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk) s = mfma32(RowTile<D>::frag(sm.k, kt, kk, l32, half), qf[kk], s);
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk) dp = mfma32(RowTile<D>::frag(sm.v, kt, kk, l32, half), gf[kk], dp);
+        const bool diag = kbase + 31 > qw0;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float pr = fast_exp2(__builtin_fmaf(s[r], c, -lse_l));
+          if (diag) {
+            const int key = kbase + 8 * (r >> 2) + 4 * half + (r & 3);
+            if (key > qpos) pr = 0.f;
+          }
+          s[r] = pr * (dp[r] - delta_l);
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const bf16x8 dsb = pack8(s[8 * u + 0], s[8 * u + 1], s[8 * u + 2], s[8 * u + 3], s[8 * u + 4],
+                                   s[8 * u + 5], s[8 * u + 6], s[8 * u + 7]);
+#pragma unroll
+          for (int dt = 0; dt < D / 32; ++dt)
+            acc[dt] = mfma32(TransposedTile<D>::frag(sm.kt, dt, 2 * kt + u, l32, half), dsb, acc[dt]);
+        }
+      }
+    }
+
+    __syncthreads();  // all wavefronts are done reading this chunk
+    if (it + 1 < total) {
+      RowTile<D>::store_quad(kreg, sm.k, tid);
+      TransposedTile<D>::store(kreg, sm.kt, tid);
+      RowTile<D>::store(vreg, sm.v, tid);
+    }
+    __syncthreads();
+  }
+
+  if (!wave_active) return;
+  uint16_t* row = p.dq + q_off + (int64_t)(qw0 + l32) * p.q_st;
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      bf16x4 w;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) w[e] = (__bf16)(acc[dt][4 * g + e] * p.scale);
+      *reinterpret_cast<bf16x4*>(row + 32 * dt + 8 * g + 4 * half) = w;
+    }
+}
+
+// ------------------------------------------------------------------------------------ dk, dv
+
+template <int D>
+struct DkvSmem {
+  uint16_t q[RowTile<D>::kElems];
+  uint16_t g[RowTile<D>::kElems];
+  uint16_t qt[TransposedTile<D>::kElems];
+  uint16_t gt[TransposedTile<D>::kElems];
+  float lse[kChunk];    // already multiplied by log2(e)
+  float delta[kChunk];
+};
+
+template <int D, bool DENSE>
+__global__ __launch_bounds__(kThreads, 1) void dkdv_kernel(const AttnParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  DkvSmem<D>& sm = *reinterpret_cast<DkvSmem<D>*>(smem_raw);
+
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+  const int T = p.kv_tiles.tiles_per_head;
+  int bh, rank;
+  if (!map_workgroup(blockIdx.x, p.batch * p.heads, T, bh, rank)) return;
+  const int b = bh / p.heads, h = bh - b * p.heads;
+  const int tile = DENSE ? rank : p.kv_tiles.order[h * T + rank];  // dense: first key tiles are longest
+  const int S = DENSE ? kChunk : p.block_size;
+  const int cpb = S / kChunk;
+  const int N = p.seqlen;
+
+  // my 32 key rows
+  int kvw0, my_member = 0;
+  bool wave_active;
+  if (DENSE) {
+    kvw0 = tile * kBwdBN + wave * 32;
+    wave_active = kvw0 < N;
+  } else {
+    my_member = (wave * 32) / S;
+    const int blk = p.kv_tiles.members[(h * T + tile) * p.kv_tiles.group + my_member];
+    wave_active = blk >= 0;
+    kvw0 = blk * S + (wave * 32) % S;
+  }
+
+  const int64_t q_off = b * p.q_sb + h * p.q_sh;
+  const int64_t kv_off = b * p.kv_sb + h * p.kv_sh;
+  const uint16_t* qb = p.q + q_off;
+  const uint16_t* gb = p.d_o + q_off;
+  const float* lse_b = p.lse + ((int64_t)b * p.heads + h) * N;
+  const float* delta_b = p.delta + ((int64_t)b * p.heads + h) * N;
+
+  bf16x8 kf[D / 16], vf[D / 16];  // K and V fragments (B operands), lane = key
+#pragma unroll
+  for (int kk = 0; kk < D / 16; ++kk) {
+    if (wave_active) {
+      const int64_t o = kv_off + (int64_t)(kvw0 + l32) * p.kv_st + 16 * kk + 8 * half;
+      kf[kk] = *reinterpret_cast<const bf16x8*>(p.k + o);
+      vf[kk] = *reinterpret_cast<const bf16x8*>(p.v + o);
+    } else {
+      kf[kk] = bf16x8{};
+      vf[kk] = bf16x8{};
+    }
+  }
+
+  int ent_lo = 0, n_ent;
+  if (DENSE) {
+    n_ent = (N - tile * kBwdBN) / kChunk;  // query chunks at or after the tile's first key
+  } else {
+    ent_lo = p.kv_tiles.ptr[h * T + tile];
+    n_ent = p.kv_tiles.ptr[h * T + tile + 1] - ent_lo;
+  }
+  const int total = n_ent * cpb;
+  auto chunk_of = [&](int it, int& q0, bool& keep) {
+    if (DENSE) {
+      q0 = tile * kBwdBN + it * kChunk;
+      keep = true;
+    } else {
+      const int e = p.kv_tiles.ent[ent_lo + it / cpb];
+      q0 = (e >> 8) * S + (it % cpb) * kChunk;
+      keep = (e >> my_member) & 1;
+    }
+  };
+
+  f32x16 acc_dk[D / 32], acc_dv[D / 32];
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt) {
+    acc_dk[dt] = f32x16{};
+    acc_dv[dt] = f32x16{};
+  }
+  const float c = p.scale_log2e;
+
+  u32x4 qreg[4], greg[4];
+  float stat = 0.f;  // threads 0..63 carry lse, 64..127 carry delta
+  auto load_chunk = [&](int q0) {
+    TransposedTile<D>::load(qreg, qb + (int64_t)q0 * p.q_st, p.q_st, tid);
+    TransposedTile<D>::load(greg, gb + (int64_t)q0 * p.q_st, p.q_st, tid);
+    if (tid < 64) stat = lse_b[q0 + tid] * kLog2e;
+    else if (tid < 128) stat = delta_b[q0 + tid - 64];
+  };
+  auto store_chunk = [&]() {
+    RowTile<D>::store_quad(qreg, sm.q, tid);
+    TransposedTile<D>::store(qreg, sm.qt, tid);
+    RowTile<D>::store_quad(greg, sm.g, tid);
+    TransposedTile<D>::store(greg, sm.gt, tid);
+    if (tid < 64) sm.lse[tid] = stat;
+    else if (tid < 128) sm.delta[tid - 64] = stat;
+  };
+
+  if (total > 0) {
+    int q0;
+    bool keep;
+    chunk_of(0, q0, keep);
+    load_chunk(q0);
+    store_chunk();
+  }
+  __syncthreads();
+
+  for (int it = 0; it < total; ++it) {
+    int q0;
+    bool keep;
+    chunk_of(it, q0, keep);
+    if (it + 1 < total) {
+      int q1;
+      bool keep1;
+      chunk_of(it + 1, q1, keep1);
+      load_chunk(q1);
+    }
+
+    if (wave_active && keep && q0 + kChunk - 1 >= kvw0) {
+      const int key = kvw0 + l32;
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt) {
+        const int qbase = q0 + 32 * qt;
+        if (qbase + 31 < kvw0) continue;  // every query of this half-chunk lies before my keys
+        f32x16 s = f32x16{}, dp = f32x16{};
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk) s = mfma32(RowTile<D>::frag(sm.q, qt, kk, l32, half), kf[kk], s);
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk) dp = mfma32(RowTile<D>::frag(sm.g, qt, kk, l32, half), vf[kk], dp);
+        const bool diag = qbase < kvw0 + 31;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int r0 = 32 * qt + 8 * g + 4 * half;
+          const f32x4 l4 = *reinterpret_cast<const f32x4*>(&sm.lse[r0]);
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(&sm.delta[r0]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int r = 4 * g + e;
+            float pr = fast_exp2(__builtin_fmaf(s[r], c, -l4[e]));
+            if (diag && key > q0 + r0 + e) pr = 0.f;
+            s[r] = pr;
+            dp[r] = pr * (dp[r] - d4[e]);
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const bf16x8 pb = pack8(s[8 * u + 0], s[8 * u + 1], s[8 * u + 2], s[8 * u + 3], s[8 * u + 4],
+                                  s[8 * u + 5], s[8 * u + 6], s[8 * u + 7]);
+          const bf16x8 dsb = pack8(dp[8 * u + 0], dp[8 * u + 1], dp[8 * u + 2], dp[8 * u + 3], dp[8 * u + 4],
+                                   dp[8 * u + 5], dp[8 * u + 6], dp[8 * u + 7]);
+#pragma unroll
+          for (int dt = 0; dt < D / 32; ++dt) {
+            acc_dv[dt] = mfma32(TransposedTile<D>::frag(sm.gt, dt, 2 * qt + u, l32, half), pb, acc_dv[dt]);
+            acc_dk[dt] = mfma32(TransposedTile<D>::frag(sm.qt, dt, 2 * qt + u, l32, half), dsb, acc_dk[dt]);
+          }
+        }
+      }
+    }
+
+    __syncthreads();
+    if (it + 1 < total) store_chunk();
+    __syncthreads();
+  }
+
+  if (!wave_active) return;
+  uint16_t* dk_row = p.dk + kv_off + (int64_t)(kvw0 + l32) * p.kv_st;
+  uint16_t* dv_row = p.dv + kv_off + (int64_t)(kvw0 + l32) * p.kv_st;
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      bf16x4 wk, wv;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        wk[e] = (__bf16)(acc_dk[dt][4 * g + e] * p.scale);
+        wv[e] = (__bf16)(acc_dv[dt][4 * g + e]);
+      }
+      *reinterpret_cast<bf16x4*>(dk_row + 32 * dt + 8 * g + 4 * half) = wk;
+      *reinterpret_cast<bf16x4*>(dv_row + 32 * dt + 8 * g + 4 * half) = wv;
+    }
+}
+
+template <class K>
+hipError_t set_smem(K kernel, size_t bytes, bool& done) {
+  if (done) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess) done = true;
+  return e;
+}
+
+template <int D, bool DENSE>
+hipError_t launch_one(const AttnParams& p, hipStream_t stream) {
+  static bool dq_set = false, dkdv_set = false;
+  hipError_t e = set_smem(&dq_kernel<D, DENSE>, sizeof(DqSmem<D>), dq_set);
+  if (e != hipSuccess) return e;
+  e = set_smem(&dkdv_kernel<D, DENSE>, sizeof(DkvSmem<D>), dkdv_set);
+  if (e != hipSuccess) return e;
+
+  const int64_t rows = (int64_t)p.batch * p.heads * p.seqlen;
+  constexpr int RPB = 256 / (D / 8);
+  hipLaunchKernelGGL((delta_kernel<D>), dim3((unsigned)((rows + RPB - 1) / RPB)), dim3(256), 0, stream, p);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int bh = p.batch * p.heads;
+  hipLaunchKernelGGL((dkdv_kernel<D, DENSE>), dim3(grid_for(bh, p.kv_tiles.tiles_per_head)), dim3(kThreads),
+                     sizeof(DkvSmem<D>), stream, p);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((dq_kernel<D, DENSE>), dim3(grid_for(bh, p.q_tiles.tiles_per_head)), dim3(kThreads),
+                     sizeof(DqSmem<D>), stream, p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_bwd(const AttnParams& p, bool dense, hipStream_t stream) {
+  if (p.head_dim == 128) return dense ? launch_one<128, true>(p, stream) : launch_one<128, false>(p, stream);
+  return dense ? launch_one<64, true>(p, stream) : launch_one<64, false>(p, stream);
+}
+
+}  // namespace s2

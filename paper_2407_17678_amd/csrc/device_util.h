@@ -75,6 +75,15 @@ struct RowTile {
       *reinterpret_cast<u32x4*>(tile + row * kStride + 8 * c) = r[n];
     }
   }
+  // registers -> LDS when the chunk was loaded with TransposedTile's thread mapping (thread holds
+  // rows 4a..4a+3, features 8c..8c+7), so one global load can feed both tile forms
+  __device__ static __forceinline__ void store_quad(const u32x4 (&r)[4], uint16_t* tile, int tid) {
+    if (tid >= 16 * (D / 8)) return;
+    const int c = (tid & 3) + 4 * (tid >> 6), a = (tid >> 2) & 15;
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+      *reinterpret_cast<u32x4*>(tile + (4 * a + n) * kStride + 8 * c) = r[n];
+  }
   // fragment: row = 32*rt + lane%32, k-slab kk (16 values of D), this lane's half
   __device__ static __forceinline__ bf16x8 frag(const uint16_t* tile, int rt, int kk, int l32, int half) {
     return *reinterpret_cast<const bf16x8*>(tile + (32 * rt + l32) * kStride + 16 * kk + 8 * half);

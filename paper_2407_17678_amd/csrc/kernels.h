@@ -11,6 +11,7 @@ struct DevTiles {
   const int32_t* ptr = nullptr;
   const int32_t* ent = nullptr;
   const int32_t* order = nullptr;
+  const int32_t* members = nullptr;  // block index of each tile member (-1 = none)
   int tiles_per_head = 0;
   int group = 0;
 };

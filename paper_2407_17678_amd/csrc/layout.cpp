@@ -133,23 +133,35 @@ void build_tiles(const s2_layout& L, int group, bool transpose, TileList& out) {
   out.ptr.assign((size_t)H * T + 1, 0);
   out.ent.clear();
   out.order.resize((size_t)H * T);
+  out.members.assign((size_t)H * T * group, -1);
   out.max_len = 0;
   std::vector<int> cur(group), end(group);
+  std::vector<int32_t> seq(B);
   for (int h = 0; h < H; ++h) {
+    const int32_t* hp0 = ptr.data() + (size_t)h * B;
+    // which blocks go together: rows stay in order; columns are sorted by how many rows keep
+    // them (longest first, ties by index) so that stripe columns pair up with stripe columns
+    std::iota(seq.begin(), seq.end(), 0);
+    if (transpose && group > 1)
+      std::stable_sort(seq.begin(), seq.end(),
+                       [&](int a, int b) { return hp0[a + 1] - hp0[a] > hp0[b + 1] - hp0[b]; });
     for (int t = 0; t < T; ++t) {
-      const int members = std::min(group, B - t * group);
-      for (int r = 0; r < members; ++r) {
-        cur[r] = ptr[(size_t)h * B + t * group + r];
-        end[r] = ptr[(size_t)h * B + t * group + r + 1];
+      const int n_members = std::min(group, B - t * group);
+      int32_t* mem = out.members.data() + ((size_t)h * T + t) * group;
+      for (int r = 0; r < n_members; ++r) mem[r] = seq[t * group + r];
+      std::sort(mem, mem + n_members);
+      for (int r = 0; r < n_members; ++r) {
+        cur[r] = hp0[mem[r]];
+        end[r] = hp0[mem[r] + 1];
       }
       const size_t start = out.ent.size();
       for (;;) {  // k-way merge of ascending lists
         int best = std::numeric_limits<int>::max();
-        for (int r = 0; r < members; ++r)
+        for (int r = 0; r < n_members; ++r)
           if (cur[r] < end[r]) best = std::min(best, (int)idx[cur[r]]);
         if (best == std::numeric_limits<int>::max()) break;
         int bits = 0;
-        for (int r = 0; r < members; ++r)
+        for (int r = 0; r < n_members; ++r)
           if (cur[r] < end[r] && idx[cur[r]] == best) { bits |= 1 << r; ++cur[r]; }
         out.ent.push_back((int32_t)((best << 8) | bits));
       }

@@ -7,19 +7,24 @@
 
 namespace s2 {
 
-// Merged tile list: consecutive groups of `group` block rows (or block columns) share one list
-// of partner blocks; each entry packs (partner_index << 8) | membership_bits, bit r set when
-// member r of the group keeps that partner.  This is the Merge-Q idea of section 3.2 (one
-// large tile serves several fine-grained mask rows) and its mirror image for key tiles.
+// Merged tile list: groups of `group` block rows (or block columns) share one list of partner
+// blocks; each entry packs (partner_index << 8) | membership_bits, bit r set when member r of
+// the group keeps that partner.  This is the Merge-Q idea of section 3.2 (one large tile serves
+// several fine-grained mask rows) and its mirror image for key tiles.  Row groups are
+// consecutive rows.  Column groups are formed from columns with similar partner sets (a stripe
+// column is attended by every later row, its neighbours only by the local window), so members
+// of a column group need not be adjacent: `members` names them.
 struct TileList {
   int group = 0;                 // members per tile (1..8)
   int tiles_per_head = 0;        // ceil(B / group)
   std::vector<int32_t> ptr;      // [H*tiles_per_head + 1]
   std::vector<int32_t> ent;      // packed entries, partner ascending inside a tile
   std::vector<int32_t> order;    // [H*tiles_per_head]: per head, tile ids by descending length
+  std::vector<int32_t> members;  // [H*tiles_per_head*group]: block index of each member, -1 = none
   int32_t* d_ptr = nullptr;      // device copies (owned by the layout)
   int32_t* d_ent = nullptr;
   int32_t* d_order = nullptr;
+  int32_t* d_members = nullptr;
   int max_len = 0;
 };
 

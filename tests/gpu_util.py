@@ -47,3 +47,23 @@ def run_fwd(w, qb, kb, vb, dense=False):
 def oracle_mask(w, H, N, dense=False):
     return orc.block_mask(H, N // w.block_size, w.local_blocks, w.stride,
                           window_blocks=w.window_blocks, dense=dense)
+
+
+def run_fwd_bwd(w, qb, kb, vb, gb, dense=False):
+    """Library forward then backward; returns dict of device tensors."""
+    q, k, v, g = to_dev(qb), to_dev(kb), to_dev(vb), to_dev(gb)
+    Bt, H, N, D = q.shape
+    o = torch.empty_like(q)
+    lse = torch.empty((Bt, H, N), dtype=torch.float32, device="cuda")
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    ws = torch.empty(B.s2_attn_bwd_workspace_bytes(Bt, H, N, D), dtype=torch.uint8, device="cuda")
+    if dense:
+        B.s2_dense_causal_fwd(q, k, v, o, lse, w.scale)
+        B.s2_dense_causal_bwd(q, k, v, o, lse, g, dq, dk, dv, w.scale, ws)
+    else:
+        lay = B.s2_layout_build(B.layout_params(H, N // w.block_size, w.block_size, w.local_blocks,
+                                                w.stride, 0, w.window_blocks, 0))
+        B.s2_attn_fwd(lay, q, k, v, o, lse, w.scale)
+        B.s2_attn_bwd(lay, q, k, v, o, lse, g, dq, dk, dv, w.scale, ws)
+    torch.cuda.synchronize()
+    return dict(o=o, lse=lse, dq=dq, dk=dk, dv=dv)

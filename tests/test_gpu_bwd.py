@@ -1,0 +1,70 @@
+"""GPU parity of the backward kernels against the fp64 oracle (through the C ABI)."""
+
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import s2_oracle as orc
+from paper_2407_17678_amd import synth
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+GRAD_TOL = 2e-2   # relative L2 bound stated for this build
+
+
+def _check_bwd(w, heads=None, batch=None, seqlen=None, dense=False):
+    qb, kb, vb, gb = synth.train_inputs(w, heads=heads, batch=batch, seqlen=seqlen)
+    Bt, H, N, D = qb.shape
+    print("bwd case", w.name, qb.shape, "S", w.block_size, "dense", dense, flush=True)
+    out = G.run_fwd_bwd(w, qb, kb, vb, gb, dense=dense)
+    M = G.oracle_mask(w, H, N, dense=dense)
+    dQ, dK, dV, O, LSE = orc.attention_backward(G.bits_f64(qb), G.bits_f64(kb), G.bits_f64(vb),
+                                                G.bits_f64(gb), M, w.block_size, w.scale)
+    errs = {n: G.rel_l2(G.to_f64(out[n]), ref) for n, ref in (("dq", dQ), ("dk", dK), ("dv", dV))}
+    print("   rel-L2", {k: "%.3e" % v for k, v in errs.items()}, flush=True)
+    for n, e in errs.items():
+        assert np.isfinite(e) and e <= GRAD_TOL, (n, e)
+    # per-(batch, head) check too, so one bad head cannot hide in the total
+    for n, ref in (("dq", dQ), ("dk", dK), ("dv", dV)):
+        got = G.to_f64(out[n])
+        for b in range(Bt):
+            for h in range(H):
+                assert G.rel_l2(got[b, h], ref[b, h]) <= GRAD_TOL, (n, b, h)
+
+
+def test_tiny_workload():
+    _check_bwd(synth.WORKLOADS["tiny"])
+
+
+@pytest.mark.parametrize("name,heads,batch,seqlen", [
+    ("1p3b_8k", 8, 2, 1024),
+    ("7b_32k", 16, 1, 2048),
+    ("7b_128k", 4, 1, 2048),
+    ("tiny", 4, 1, 576),
+    ("1p3b_8k", 3, 3, 64),
+])
+def test_small_cases(name, heads, batch, seqlen):
+    _check_bwd(synth.WORKLOADS[name], heads=heads, batch=batch, seqlen=seqlen)
+
+
+@pytest.mark.parametrize("name,heads,seqlen", [("tiny", 4, 512), ("1p3b_8k", 2, 1024)])
+def test_dense_causal(name, heads, seqlen):
+    _check_bwd(synth.WORKLOADS[name], heads=heads, batch=1, seqlen=seqlen, dense=True)
+
+
+def test_variants_window_and_swa():
+    base = synth.WORKLOADS["1p3b_8k"]
+    for kw in (dict(stride=0), dict(window_blocks=6), dict(local_blocks=1, stride=3)):
+        _check_bwd(dataclasses.replace(base, **kw), heads=4, batch=1, seqlen=1024)
+
+
+def test_backward_is_bitwise_repeatable():
+    w = synth.WORKLOADS["1p3b_8k"]
+    qb, kb, vb, gb = synth.train_inputs(w, heads=8, batch=1, seqlen=1024)
+    a = G.run_fwd_bwd(w, qb, kb, vb, gb)
+    b = G.run_fwd_bwd(w, qb, kb, vb, gb)
+    for n in ("o", "lse", "dq", "dk", "dv"):
+        assert torch.equal(a[n], b[n]), n
