@@ -1,0 +1,327 @@
+#!/usr/bin/env python3
+"""Benchmark of the S2-Attention / HHST hot path on one MI355X.
+
+A step is one forward + backward pass of head-heterogeneous block-sparse causal
+attention over one batch of synthetic bf16 tensors that are already resident in
+HBM.  Prints ONE JSON line: effective (unmasked) TFLOP/s of forward+backward,
+its fraction of the bf16 MFMA peak, the speed-up over the library's own dense
+causal kernels, a roofline record for the dominant kernel (timed here with HIP
+events, one kernel per launch) and the CPU oracle's rate on a bounded sample.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 7b_32k]
+"""
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def sparse_pairs(nnz, H, B, S):
+    """Unmasked (query, key) pairs of one batch element: diagonal blocks are triangular."""
+    return (nnz - H * B) * S * S + H * B * S * (S + 1) // 2
+
+
+def time_events(fn, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def bench_train(w, steps, warmup, with_dense=True, with_bwd=True, dense_steps=3):
+    """Times fwd(+bwd) of workload `w`; returns a dict of timings and derived rates."""
+    import torch
+    from paper_2407_17678_amd import binding as B
+    from paper_2407_17678_amd import synth
+
+    t0 = time.time()
+    qb, kb, vb, gb = synth.train_inputs(w)
+    q, k, v, g = (B.bf16_bits_to_device(x) for x in (qb, kb, vb, gb))
+    log("[bench] %s: inputs %s generated in %.1fs" % (w.name, tuple(q.shape), time.time() - t0))
+    Bt, H, N, D = q.shape
+    S = w.block_size
+    o = torch.empty_like(q)
+    lse = torch.empty((Bt, H, N), dtype=torch.float32, device="cuda")
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    ws = torch.empty(B.s2_attn_bwd_workspace_bytes(Bt, H, N, D), dtype=torch.uint8, device="cuda")
+    t0 = time.time()
+    lay = B.s2_layout_build(B.layout_params(H, N // S, S, w.local_blocks, w.stride, 0, w.window_blocks, 0))
+    layout_ms = (time.time() - t0) * 1e3
+    nnz = B.s2_layout_get(lay)["nnz"]
+    pairs = sparse_pairs(nnz, H, N // S, S) * Bt
+    dense_pairs = H * N * (N + 1) // 2 * Bt
+
+    fwd = lambda: B.s2_attn_fwd(lay, q, k, v, o, lse, w.scale)
+    bwd = lambda: B.s2_attn_bwd(lay, q, k, v, o, lse, g, dq, dk, dv, w.scale, ws)
+    stage = lambda s: (lambda: B.s2_attn_bwd_stages(lay, q, k, v, o, lse, g, dq, dk, dv, w.scale, ws, s))
+
+    def step():
+        fwd()
+        if with_bwd:
+            bwd()
+
+    # the timed region: exactly `steps` steps between two synchronisations
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_wall = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_wall) * 1e3 / steps
+    ms_step = e0.elapsed_time(e1) / steps
+
+    res = dict(workload=w.name, batch=Bt, heads=H, seqlen=N, head_dim=D, block_size=S,
+               local_blocks=w.local_blocks, stride=w.stride, nnz_blocks=int(nnz),
+               layout_build_ms=round(layout_ms, 2), ms_per_step=ms_step, wall_ms_per_step=wall_ms)
+    # each kernel on its own (same stream, same inputs)
+    res["ms_fwd"] = time_events(fwd, steps, 1)
+    flops_fwd = 4.0 * D * pairs
+    if with_bwd:
+        res["ms_bwd_delta"] = time_events(stage(B.BWD_DELTA), steps, 1)
+        res["ms_bwd_dkdv"] = time_events(stage(B.BWD_DKDV), steps, 1)
+        res["ms_bwd_dq"] = time_events(stage(B.BWD_DQ), steps, 1)
+        flops = 14.0 * D * pairs
+    else:
+        flops = flops_fwd
+    res["effective_gflop"] = flops / 1e9
+    res["tflops"] = flops / (ms_step * 1e-3) / 1e12
+    res["tflops_fwd"] = flops_fwd / (res["ms_fwd"] * 1e-3) / 1e12
+    res["pct_mfma_peak"] = 100.0 * res["tflops"] / PEAK_BF16_TFLOPS
+    res["pair_ratio_dense_over_sparse"] = dense_pairs / pairs
+
+    if with_dense:
+        dfwd = lambda: B.s2_dense_causal_fwd(q, k, v, o, lse, w.scale)
+        dbwd = lambda: B.s2_dense_causal_bwd(q, k, v, o, lse, g, dq, dk, dv, w.scale, ws)
+
+        def dstep():
+            dfwd()
+            if with_bwd:
+                dbwd()
+        res["dense_ms_per_step"] = time_events(dstep, dense_steps, 1)
+        res["dense_ms_fwd"] = time_events(dfwd, dense_steps, 0)
+        dflops = (14.0 if with_bwd else 4.0) * D * dense_pairs
+        res["dense_tflops"] = dflops / (res["dense_ms_per_step"] * 1e-3) / 1e12
+        res["speedup_vs_dense"] = res["dense_ms_per_step"] / ms_step
+        res["speedup_vs_dense_fwd"] = res["dense_ms_fwd"] / res["ms_fwd"]
+        step()  # leave the sparse path's outputs in place for the parity sample
+
+    # roofline of the dominant kernel.  Flops attributed per kernel (sums to 14*D*pairs):
+    # forward 4*D*pairs (QK^T, PV); dK/dV kernel 8*D*pairs (S, dP, dV, dK); dQ kernel 2*D*pairs.
+    kernels = {"fwd_kernel": (res["ms_fwd"], 4.0)}
+    if with_bwd:
+        kernels["dkdv_kernel"] = (res["ms_bwd_dkdv"], 8.0)
+        kernels["dq_kernel"] = (res["ms_bwd_dq"], 2.0)
+    dom = max(kernels, key=lambda n: kernels[n][0])
+    ach = kernels[dom][1] * D * pairs / (kernels[dom][0] * 1e-3) / 1e12
+    res["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
+                       "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
+                       "avg_launch_ms": kernels[dom][0],
+                       "algorithmic_flops_per_launch": kernels[dom][1] * D * pairs}
+    tensors = dict(q=q, k=k, v=v, g=g, o=o, lse=lse, dq=dq, dk=dk, dv=dv, bits=(qb, kb, vb, gb))
+    return res, tensors
+
+
+def cpu_baseline_train(w, tensors, sample_tokens, with_bwd=True):
+    """The oracle, untuned, on head 0 of batch 0 restricted to the first `sample_tokens` tokens
+    (a causal prefix is self-contained); also compares the GPU's O / LSE / dQ on that prefix."""
+    from oracle import s2_oracle as orc
+    from paper_2407_17678_amd import synth
+    qb, kb, vb, gb = tensors["bits"]
+    n = min(sample_tokens, qb.shape[2])
+    S = w.block_size
+    f64 = lambda x: synth.bf16_bits_to_f32(x[0, 0, :n]).astype(np.float64)
+    q, k, v, g = f64(qb), f64(kb), f64(vb), f64(gb)
+    M = orc.block_mask(1, n // S, w.local_blocks, w.stride, window_blocks=w.window_blocks)
+    pairs = orc.unmasked_pairs(M, S, n)
+    t0 = time.perf_counter()
+    if with_bwd:
+        dQ, dK, dV, O, LSE = orc.attention_backward_head(q, k, v, g, M[0], S, w.scale)
+    else:
+        O, LSE = orc.attention_forward_head(q, k, v, M[0], S, w.scale)
+    sec = time.perf_counter() - t0
+    flops = (14.0 if with_bwd else 4.0) * w.head_dim * pairs
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count()
+    threads = cores
+    try:
+        from threadpoolctl import threadpool_info
+        blas = [i["num_threads"] for i in threadpool_info() if i.get("user_api") == "blas"]
+        if blas:
+            threads = max(blas)
+    except Exception:
+        pass
+    go = tensors["o"][0, 0, :n].float().cpu().numpy().astype(np.float64)
+    gl = tensors["lse"][0, 0, :n].cpu().numpy().astype(np.float64)
+    # bound on O: 1e-2, widened to half a bf16 ulp where |O| >= 4 makes that larger
+    excess = np.abs(go - O) - np.maximum(1e-2, np.abs(O) * 2.0 ** -8)
+    parity = {"o_max_abs": float(np.abs(go - O).max()), "o_max_excess_over_bound": float(excess.max()),
+              "lse_max_abs": float(np.abs(gl - LSE).max())}
+    if with_bwd:
+        gq = tensors["dq"][0, 0, :n].float().cpu().numpy().astype(np.float64)
+        parity["dq_rel_l2"] = float(np.linalg.norm(gq - dQ) / np.linalg.norm(dQ))
+        if n == qb.shape[2]:   # dK, dV need every query of the head
+            for name, ref in (("dk", dK), ("dv", dV)):
+                gg = tensors[name][0, 0].float().cpu().numpy().astype(np.float64)
+                parity[name + "_rel_l2"] = float(np.linalg.norm(gg - ref) / np.linalg.norm(ref))
+    return {"value": flops / sec / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "sample": "head 0 of batch 0, first %d tokens, %s, fp64 numpy" % (n, "fwd+bwd" if with_bwd else "fwd"),
+            "seconds": sec, "host_cores_visible": int(cores)}, parity
+
+
+def bench_decode(w, steps, warmup):
+    import torch
+    from paper_2407_17678_amd import binding as B
+    from paper_2407_17678_amd import synth
+    nseq, H, D, max_len = w.batch, w.heads, w.head_dim, w.max_len
+    lens = synth.decode_lengths(w)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.BASE_SEED + w.index)
+    q = torch.randn((nseq, H, D), device="cuda", generator=gen).to(torch.bfloat16)
+    kc = torch.empty((nseq, H, max_len, D), dtype=torch.bfloat16, device="cuda")
+    vc = torch.empty_like(kc)
+    for b in range(nseq):   # fill in slices so that the fp32 temporaries stay small
+        kc[b] = torch.randn((H, max_len, D), device="cuda", generator=gen).to(torch.bfloat16)
+        vc[b] = torch.randn((H, max_len, D), device="cuda", generator=gen).to(torch.bfloat16)
+    sl = torch.from_numpy(lens).cuda()
+    o = torch.empty_like(q)
+    lse = torch.empty((nseq, H), dtype=torch.float32, device="cuda")
+    p = B.layout_params(H, 1, w.block_size, w.local_blocks, w.stride, 0, w.window_blocks, 0)
+    splits = B.s2_attn_decode_default_splits(nseq, H, max_len)
+    ws = torch.empty(B.s2_attn_decode_workspace_bytes(nseq, H, D, max_len, splits), dtype=torch.uint8,
+                     device="cuda")
+    run = lambda: B.s2_attn_decode(p, q, kc, vc, sl, o, lse, w.scale, ws, max_len, num_splits=splits)
+    ms = time_events(run, steps, warmup)
+    # algorithmic bytes: K and V rows of the kept tokens, plus q, o and the split partials
+    S = w.block_size
+    tokens = 0
+    for L in lens.tolist():
+        i = (L - 1) // S
+        for h in range(H):
+            o_h = h % w.stride
+            local_lo = max(0, i - w.local_blocks + 1)
+            n_str = (local_lo - 1 - o_h) // w.stride + 1 if o_h < local_lo else 0
+            tokens += n_str * S + (L - local_lo * S)
+    kv_bytes = tokens * D * 2 * 2
+    other = nseq * H * D * 2 * 2 + 2 * nseq * H * splits * (D + 2) * 4
+    dense_bytes = int(lens.astype(np.int64).sum()) * H * D * 2 * 2
+    gbs = (kv_bytes + other) / (ms * 1e-3) / 1e9
+    return dict(workload=w.name, nseq=nseq, heads=H, head_dim=D, max_len=max_len, splits=int(splits),
+                mean_len=float(lens.mean()), ms=ms, kept_tokens=int(tokens), algorithmic_gb=(kv_bytes + other) / 1e9,
+                dense_gb=dense_bytes / 1e9, hbm_gbs=gbs, frac_hbm_peak=gbs / PEAK_HBM_GBS)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="7b_32k", choices=["tiny", "1p3b_8k", "7b_32k", "7b_128k", "7b_decode"])
+    ap.add_argument("--cpu-sample-tokens", type=int, default=32768)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--extra", action="store_true", help="also time the other workloads (reported under 'extra')")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU; --gpus %d is not supported (heads and batch "
+                 "shard without communication, see DESIGN.md)" % args.gpus)
+    if int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: launched with WORLD_SIZE > 1; this build runs on one GPU")
+
+    import torch
+    from paper_2407_17678_amd import binding as B
+    from paper_2407_17678_amd import synth
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP library is the only path")
+    B.lib()
+    torch.cuda.set_device(0)
+    w = synth.WORKLOADS[args.workload]
+
+    if w.kind == "decode":
+        d = bench_decode(w, args.steps, args.warmup)
+        out = {"metric": "decode HBM GB/s (algorithmic K+V bytes of kept blocks)", "value": d["hbm_gbs"],
+               "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": d["ms"],
+               "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+               "data": "synthetic", "config": d,
+               "roofline": {"kernel": "decode_split_kernel", "bound": "hbm", "achieved": d["hbm_gbs"],
+                            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": d["frac_hbm_peak"], "traffic": None},
+               "cpu_baseline": None}
+        print(json.dumps(out))
+        return
+
+    with_bwd = w.name != "7b_128k"
+    res, tensors = bench_train(w, args.steps, args.warmup, with_dense=not args.no_dense, with_bwd=with_bwd,
+                               dense_steps=2 if w.seqlen > 40000 else 3)
+    roof = res.pop("roofline")
+    cpu, parity = None, None
+    if not args.no_cpu_baseline:
+        log("[bench] timing the CPU oracle on a %d-token prefix of one head ..." % args.cpu_sample_tokens)
+        cpu, parity = cpu_baseline_train(w, tensors, args.cpu_sample_tokens, with_bwd=with_bwd)
+        log("[bench] oracle: %.1fs on %d threads; parity on the sample: %s" % (cpu["seconds"], cpu["cores"], parity))
+    del tensors
+    torch.cuda.empty_cache()
+
+    extra = None
+    if args.extra:
+        extra = {}
+        for name in ("1p3b_8k", "7b_32k", "7b_128k"):
+            if name == w.name:
+                continue
+            ww = synth.WORKLOADS[name]
+            r, t = bench_train(ww, max(3, args.steps // 2), 2, with_dense=not args.no_dense,
+                               with_bwd=name != "7b_128k", dense_steps=1 if name == "7b_128k" else 3)
+            r.pop("roofline")
+            extra[name] = r
+            del t
+            torch.cuda.empty_cache()
+        extra["7b_decode"] = bench_decode(synth.WORKLOADS["7b_decode"], 20, 3)
+
+    out = {
+        "metric": "effective sparse-attn TFLOP/s fwd+bwd (% MFMA peak) + speedup vs dense causal"
+                  if with_bwd else "effective sparse-attn TFLOP/s fwd (% MFMA peak) + speedup vs dense causal",
+        "value": res["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "batch": res["batch"], "heads": res["heads"], "seq_len": res["seqlen"],
+                   "head_dim": res["head_dim"], "block_size": res["block_size"],
+                   "local_blocks": res["local_blocks"], "stride": res["stride"], "pass": "fwd+bwd" if with_bwd else "fwd"},
+        "pct_mfma_peak": res["pct_mfma_peak"],
+        "speedup_vs_dense": res.get("speedup_vs_dense"),
+        "detail": res,
+        "roofline": roof,
+        "cpu_baseline": cpu,
+        "parity_on_cpu_sample": parity,
+    }
+    if extra is not None:
+        out["extra"] = extra
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -65,7 +65,7 @@ class DecodeArgs(C.Structure):
 
 EXPORTS = (
     "s2_layout_build", "s2_layout_destroy", "s2_layout_get", "s2_attn_fwd", "s2_attn_bwd",
-    "s2_attn_bwd_workspace_bytes", "s2_dense_causal_fwd", "s2_dense_causal_bwd", "s2_attn_decode",
+    "s2_attn_bwd_workspace_bytes", "s2_attn_bwd_stages", "s2_dense_causal_fwd", "s2_dense_causal_bwd", "s2_attn_decode",
     "s2_attn_decode_workspace_bytes", "s2_attn_decode_default_splits", "s2_status_string",
     "s2_last_hip_error", "s2_version",
 )
@@ -86,6 +86,8 @@ def lib():
     L.s2_layout_get.argtypes = [C.c_void_p, C.POINTER(LayoutView)]
     L.s2_attn_fwd.argtypes = [C.c_void_p, C.POINTER(Tensors), C.c_float, C.c_void_p]
     L.s2_attn_bwd.argtypes = [C.c_void_p, C.POINTER(Tensors), C.c_float, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.s2_attn_bwd_stages.argtypes = [C.c_void_p, C.POINTER(Tensors), C.c_float, C.c_void_p, C.c_size_t,
+                                     C.c_int, C.c_void_p]
     L.s2_attn_bwd_workspace_bytes.argtypes = [C.c_int32] * 4
     L.s2_attn_bwd_workspace_bytes.restype = C.c_size_t
     L.s2_dense_causal_fwd.argtypes = [C.POINTER(Tensors), C.c_float, C.c_void_p]
@@ -165,6 +167,13 @@ def s2_layout_get(layout):
     }
 
 
+def bf16_bits_to_device(bits, device="cuda"):
+    """uint16 bf16 bit patterns (numpy) -> torch.bfloat16 tensor on the GPU holding the same bits."""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device)
+    return t.view(torch.bfloat16)
+
+
 def _ptr(t):
     return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(None)
 
@@ -194,6 +203,16 @@ def s2_attn_bwd(layout, q, k, v, o, lse, d_o, dq, dk, dv, scale, workspace, stre
     _check(lib().s2_attn_bwd(layout.handle, C.byref(t), scale, _ptr(workspace),
                              workspace.numel() * workspace.element_size(), _stream_ptr(stream)),
            "s2_attn_bwd")
+
+
+BWD_DELTA, BWD_DKDV, BWD_DQ, BWD_ALL = 1, 2, 4, 7
+
+
+def s2_attn_bwd_stages(layout, q, k, v, o, lse, d_o, dq, dk, dv, scale, workspace, stages, stream=None):
+    t = _tensors(q, k, v, o, lse, d_o, dq, dk, dv)
+    _check(lib().s2_attn_bwd_stages(layout.handle, C.byref(t), scale, _ptr(workspace),
+                                    workspace.numel() * workspace.element_size(), stages,
+                                    _stream_ptr(stream)), "s2_attn_bwd_stages")
 
 
 def s2_dense_causal_fwd(q, k, v, o, lse, scale, stream=None):

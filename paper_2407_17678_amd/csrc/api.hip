@@ -200,7 +200,13 @@ size_t s2_attn_bwd_workspace_bytes(int32_t batch, int32_t heads, int32_t seqlen,
 
 int s2_attn_bwd(const s2_layout* layout, const s2_tensors* t, float scale, void* workspace,
                 size_t workspace_bytes, void* stream) {
+  return s2_attn_bwd_stages(layout, t, scale, workspace, workspace_bytes, S2_BWD_ALL, stream);
+}
+
+int s2_attn_bwd_stages(const s2_layout* layout, const s2_tensors* t, float scale, void* workspace,
+                       size_t workspace_bytes, int stages, void* stream) {
   if (!layout) return S2_ERR_NULL;
+  if (stages < 1 || stages > S2_BWD_ALL) return S2_ERR_BAD_PARAM;
   int st = check_tensors(t, true, scale);
   if (st != S2_OK) return st;
   st = check_layout_fits(layout, t);
@@ -214,7 +220,7 @@ int s2_attn_bwd(const s2_layout* layout, const s2_tensors* t, float scale, void*
   p.block_size = layout->p.block_size;
   p.q_tiles = dev_tiles(layout->q_tiles);
   p.kv_tiles = dev_tiles(layout->kv_tiles);
-  return hip_ok(s2::launch_bwd(p, false, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
+  return hip_ok(s2::launch_bwd(p, false, stages, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
 }
 
 static int dense_params(const s2_tensors* t, s2::AttnParams& p) {
@@ -247,7 +253,7 @@ int s2_dense_causal_bwd(const s2_tensors* t, float scale, void* workspace, size_
   st = dense_params(t, p);
   if (st != S2_OK) return st;
   p.delta = static_cast<float*>(workspace);
-  return hip_ok(s2::launch_bwd(p, true, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
+  return hip_ok(s2::launch_bwd(p, true, s2::kBwdAll, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
 }
 
 int32_t s2_attn_decode_default_splits(int32_t nseq, int32_t heads, int32_t max_len) {

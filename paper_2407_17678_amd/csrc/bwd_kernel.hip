@@ -408,7 +408,7 @@ hipError_t set_smem(K kernel, size_t bytes, bool& done) {
 }
 
 template <int D, bool DENSE>
-hipError_t launch_one(const AttnParams& p, hipStream_t stream) {
+hipError_t launch_one(const AttnParams& p, int stages, hipStream_t stream) {
   static bool dq_set = false, dkdv_set = false;
   hipError_t e = set_smem(&dq_kernel<D, DENSE>, sizeof(DqSmem<D>), dq_set);
   if (e != hipSuccess) return e;
@@ -417,24 +417,32 @@ hipError_t launch_one(const AttnParams& p, hipStream_t stream) {
 
   const int64_t rows = (int64_t)p.batch * p.heads * p.seqlen;
   constexpr int RPB = 256 / (D / 8);
-  hipLaunchKernelGGL((delta_kernel<D>), dim3((unsigned)((rows + RPB - 1) / RPB)), dim3(256), 0, stream, p);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  if (stages & kBwdDelta) {
+    hipLaunchKernelGGL((delta_kernel<D>), dim3((unsigned)((rows + RPB - 1) / RPB)), dim3(256), 0, stream, p);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   const int bh = p.batch * p.heads;
-  hipLaunchKernelGGL((dkdv_kernel<D, DENSE>), dim3(grid_for(bh, p.kv_tiles.tiles_per_head)), dim3(kThreads),
-                     sizeof(DkvSmem<D>), stream, p);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((dq_kernel<D, DENSE>), dim3(grid_for(bh, p.q_tiles.tiles_per_head)), dim3(kThreads),
-                     sizeof(DqSmem<D>), stream, p);
-  return hipGetLastError();
+  if (stages & kBwdDkDv) {
+    hipLaunchKernelGGL((dkdv_kernel<D, DENSE>), dim3(grid_for(bh, p.kv_tiles.tiles_per_head)),
+                       dim3(kThreads), sizeof(DkvSmem<D>), stream, p);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  if (stages & kBwdDq) {
+    hipLaunchKernelGGL((dq_kernel<D, DENSE>), dim3(grid_for(bh, p.q_tiles.tiles_per_head)), dim3(kThreads),
+                       sizeof(DqSmem<D>), stream, p);
+    e = hipGetLastError();
+  }
+  return e;
 }
 
 }  // namespace
 
-hipError_t launch_bwd(const AttnParams& p, bool dense, hipStream_t stream) {
-  if (p.head_dim == 128) return dense ? launch_one<128, true>(p, stream) : launch_one<128, false>(p, stream);
-  return dense ? launch_one<64, true>(p, stream) : launch_one<64, false>(p, stream);
+hipError_t launch_bwd(const AttnParams& p, bool dense, int stages, hipStream_t stream) {
+  if (p.head_dim == 128)
+    return dense ? launch_one<128, true>(p, stages, stream) : launch_one<128, false>(p, stages, stream);
+  return dense ? launch_one<64, true>(p, stages, stream) : launch_one<64, false>(p, stages, stream);
 }
 
 }  // namespace s2

@@ -10,8 +10,7 @@ from paper_2407_17678_amd import synth
 
 def to_dev(bits):
     """uint16 bf16 bit patterns (numpy) -> torch.bfloat16 tensor on cuda:0 with the same bits."""
-    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
-    return t.view(torch.bfloat16)
+    return B.bf16_bits_to_device(bits)
 
 
 def to_f64(t):
@@ -21,6 +20,12 @@ def to_f64(t):
 
 def bits_f64(bits):
     return synth.bf16_bits_to_f32(bits).astype(np.float64)
+
+
+def o_excess(got, want):
+    """Largest |got - want| minus the bound on O: 1e-2, widened to half a bf16 ulp (2^-8 |O|)
+    where |O| >= 4 makes a bf16 output unable to do better.  Passing means <= 0."""
+    return float((np.abs(got - want) - np.maximum(1e-2, np.abs(want) * 2.0 ** -8)).max())
 
 
 def rel_l2(got, want):
