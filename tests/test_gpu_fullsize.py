@@ -1,0 +1,125 @@
+"""Parity at the full workload sizes, in the launch configuration bench.py times.
+
+The oracle cannot afford every output at these sizes, so: forward rows are independent and are
+sampled (each sampled row is computed by the oracle from all N keys); the backward is checked on
+whole heads (one head of the 32K workload costs the oracle about ten seconds)."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import s2_oracle as orc
+from paper_2407_17678_amd import binding as B
+from paper_2407_17678_amd import synth
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+def _sample_rows(N, S, B_l, rng, n_random=24):
+    fixed = [0, 1, S - 1, S, S * B_l - 1, S * B_l, S * B_l + 1, N // 2, N - S - 1, N - S, N - 1]
+    rows = sorted(set(fixed) | set(int(x) for x in rng.integers(0, N, size=n_random)))
+    return np.array(rows)
+
+
+def _check_forward_rows(w, o, lse, bits, heads, rng):
+    qb, kb, vb = bits
+    N, S = w.seqlen, w.block_size
+    M = orc.block_mask(w.heads, N // S, w.local_blocks, w.stride)
+    for (b, h) in heads:
+        rows = _sample_rows(N, S, w.local_blocks, rng)
+        f = lambda x: G.bits_f64(x[b, h])
+        O, LSE = orc.forward_rows(f(qb)[rows], rows, f(kb), f(vb), M[h], S, w.scale)
+        go = G.to_f64(o[b, h][torch.from_numpy(rows).cuda()])
+        gl = G.to_f64(lse[b, h][torch.from_numpy(rows).cuda()])
+        assert G.o_excess(go, O) <= 0, (b, h)
+        assert np.abs(gl - LSE).max() <= 1e-3, (b, h)
+
+
+def _check_backward_head(w, out, bits, b, h):
+    qb, kb, vb, gb = bits
+    S = w.block_size
+    M = orc.block_mask(w.heads, w.seqlen // S, w.local_blocks, w.stride)
+    f = lambda x: G.bits_f64(x[b, h])
+    dQ, dK, dV, O, LSE = orc.attention_backward_head(f(qb), f(kb), f(vb), f(gb), M[h], S, w.scale)
+    assert G.o_excess(G.to_f64(out["o"][b, h]), O) <= 0
+    assert np.abs(G.to_f64(out["lse"][b, h]) - LSE).max() <= 1e-3
+    for n, ref in (("dq", dQ), ("dk", dK), ("dv", dV)):
+        e = G.rel_l2(G.to_f64(out[n][b, h]), ref)
+        print("   %s head (%d,%d) rel-L2 %.3e" % (n, b, h, e), flush=True)
+        assert e <= 2e-2, (n, b, h, e)
+
+
+def test_1p3b_8k_full():
+    w = synth.WORKLOADS["1p3b_8k"]
+    print("full-size case", w.name, flush=True)
+    bits = synth.train_inputs(w)
+    out = G.run_fwd_bwd(w, *bits)
+    rng = np.random.default_rng(1)
+    _check_forward_rows(w, out["o"], out["lse"], bits[:3], [(0, 0), (1, 5), (2, 7), (3, 15)], rng)
+    for (b, h) in [(0, 0), (3, 15), (1, 6)]:
+        _check_backward_head(w, out, bits, b, h)
+    # every output finite and nothing left unwritten
+    for n in ("o", "dq", "dk", "dv"):
+        assert torch.isfinite(out[n].float()).all()
+
+
+def test_7b_32k_full():
+    w = synth.WORKLOADS["7b_32k"]
+    print("full-size case", w.name, flush=True)
+    bits = synth.train_inputs(w)
+    out = G.run_fwd_bwd(w, *bits)
+    rng = np.random.default_rng(2)
+    _check_forward_rows(w, out["o"], out["lse"], bits[:3], [(0, h) for h in (0, 5, 15, 16, 31)], rng)
+    _check_backward_head(w, out, bits, 0, 21)
+    for n in ("o", "dq", "dk", "dv"):
+        assert torch.isfinite(out[n].float()).all()
+
+
+def test_7b_128k_forward_full():
+    w = synth.WORKLOADS["7b_128k"]
+    print("full-size case", w.name, flush=True)
+    rngs = synth.rng_for(w.index)
+    shape = (w.batch, w.heads, w.seqlen, w.head_dim)
+    qb, kb, vb = (synth.normal_bf16(rngs, shape) for _ in range(3))
+    o, lse, _, _ = G.run_fwd(w, qb, kb, vb)
+    rng = np.random.default_rng(3)
+    _check_forward_rows(w, o, lse, (qb, kb, vb), [(0, h) for h in (0, 7, 31)], rng)
+    assert torch.isfinite(o.float()).all()
+
+
+def test_7b_decode_full():
+    """64 sequences x 32 heads against a 34 GB cache filled on the device; the oracle checks a
+    sample of (sequence, head) pairs from slices copied back."""
+    w = synth.WORKLOADS["7b_decode"]
+    print("full-size case", w.name, flush=True)
+    nseq, H, D, max_len = w.batch, w.heads, w.head_dim, w.max_len
+    lens = synth.decode_lengths(w)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.BASE_SEED + w.index)
+    q = torch.randn((nseq, H, D), device="cuda", generator=gen).to(torch.bfloat16)
+    kc = torch.empty((nseq, H, max_len, D), dtype=torch.bfloat16, device="cuda")
+    vc = torch.empty_like(kc)
+    for b in range(nseq):
+        kc[b] = torch.randn((H, max_len, D), device="cuda", generator=gen).to(torch.bfloat16)
+        vc[b] = torch.randn((H, max_len, D), device="cuda", generator=gen).to(torch.bfloat16)
+    sl = torch.from_numpy(lens).cuda()
+    o = torch.empty_like(q)
+    lse = torch.empty((nseq, H), dtype=torch.float32, device="cuda")
+    p = B.layout_params(H, 1, w.block_size, w.local_blocks, w.stride)
+    splits = B.s2_attn_decode_default_splits(nseq, H, max_len)
+    ws = torch.empty(B.s2_attn_decode_workspace_bytes(nseq, H, D, max_len, splits), dtype=torch.uint8,
+                     device="cuda")
+    B.s2_attn_decode(p, q, kc, vc, sl, o, lse, w.scale, ws, max_len, num_splits=splits)
+    torch.cuda.synchronize()
+    assert torch.isfinite(o.float()).all()
+    rng = np.random.default_rng(4)
+    pairs = {(int(np.argmin(lens)), 0), (int(np.argmax(lens)), 31)}
+    while len(pairs) < 24:
+        pairs.add((int(rng.integers(0, nseq)), int(rng.integers(0, H))))
+    for (b, h) in sorted(pairs):
+        L = int(lens[b])
+        ref, ref_lse = orc.decode_row(G.to_f64(q[b, h]), G.to_f64(kc[b, h, :L]), G.to_f64(vc[b, h, :L]), L, h,
+                                      w.block_size, w.local_blocks, w.stride, w.scale)
+        assert G.o_excess(G.to_f64(o[b, h]), ref) <= 0, (b, h)
+        assert abs(float(lse[b, h]) - ref_lse) <= 1e-3, (b, h)
