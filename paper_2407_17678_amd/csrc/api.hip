@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -122,7 +123,8 @@ int s2_layout_build(const s2_layout_params* params, s2_layout** out) {
   try {
     st = s2::build_host(*params, *L);
     if (st == S2_OK) {
-      s2::build_tiles(*L, s2::kFwdBM / params->block_size, false, L->q_tiles);
+      s2::build_tiles(*L, s2::kFwdBM / params->block_size, false, L->fwd_tiles);
+      s2::build_tiles(*L, s2::kBwdBM / params->block_size, false, L->q_tiles);
       s2::build_tiles(*L, s2::kBwdBN / params->block_size, true, L->kv_tiles);
     }
   } catch (const std::bad_alloc&) {
@@ -135,8 +137,10 @@ int s2_layout_build(const s2_layout_params* params, s2_layout** out) {
   int ndev = 0;
   if (hipGetDeviceCount(&ndev) == hipSuccess && ndev > 0) {
     int dev = 0;
-    bool ok = hip_ok(hipGetDevice(&dev)) && upload_tiles(L->q_tiles) && upload_tiles(L->kv_tiles);
+    bool ok = hip_ok(hipGetDevice(&dev)) && upload_tiles(L->fwd_tiles) && upload_tiles(L->q_tiles) &&
+              upload_tiles(L->kv_tiles);
     if (!ok) {
+      free_tiles(L->fwd_tiles);
       free_tiles(L->q_tiles);
       free_tiles(L->kv_tiles);
       delete L;
@@ -154,6 +158,7 @@ int s2_layout_build(const s2_layout_params* params, s2_layout** out) {
 int s2_layout_destroy(s2_layout* layout) {
   if (!layout) return S2_ERR_NULL;
   if (layout->on_device) {
+    free_tiles(layout->fwd_tiles);
     free_tiles(layout->q_tiles);
     free_tiles(layout->kv_tiles);
   }
@@ -186,16 +191,19 @@ int s2_attn_fwd(const s2_layout* layout, const s2_tensors* t, float scale, void*
   if (!layout->on_device) return S2_ERR_NO_DEVICE;
   s2::AttnParams p = make_params(t, scale);
   p.block_size = layout->p.block_size;
+  p.fwd_tiles = dev_tiles(layout->fwd_tiles);
   p.q_tiles = dev_tiles(layout->q_tiles);
   p.kv_tiles = dev_tiles(layout->kv_tiles);
-  return hip_ok(s2::launch_fwd(p, false, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
+  if (getenv("S2_FWD_V1")) return hip_ok(s2::launch_fwd(p, false, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
+  return hip_ok(s2::launch_fwd2(p, false, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
 }
 
 size_t s2_attn_bwd_workspace_bytes(int32_t batch, int32_t heads, int32_t seqlen, int32_t head_dim) {
   (void)head_dim;
   if (batch < 1 || heads < 1 || seqlen < 1) return 0;
   const size_t rows = (size_t)batch * heads * seqlen;
-  return ((rows * sizeof(float) + 255) / 256) * 256;  // delta = rowsum(dO * O)
+  // delta = rowsum(dO * O) and a copy of LSE in base-2 units, 256-byte aligned each
+  return 2 * (((rows * sizeof(float) + 255) / 256) * 256);
 }
 
 int s2_attn_bwd(const s2_layout* layout, const s2_tensors* t, float scale, void* workspace,
@@ -217,7 +225,9 @@ int s2_attn_bwd_stages(const s2_layout* layout, const s2_tensors* t, float scale
   if (!layout->on_device) return S2_ERR_NO_DEVICE;
   s2::AttnParams p = make_params(t, scale);
   p.delta = static_cast<float*>(workspace);
+  p.lse2 = p.delta + s2_attn_bwd_workspace_bytes(t->batch, t->heads, t->seqlen, t->head_dim) / 8;
   p.block_size = layout->p.block_size;
+  p.fwd_tiles = dev_tiles(layout->fwd_tiles);
   p.q_tiles = dev_tiles(layout->q_tiles);
   p.kv_tiles = dev_tiles(layout->kv_tiles);
   return hip_ok(s2::launch_bwd(p, false, stages, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
@@ -226,8 +236,10 @@ int s2_attn_bwd_stages(const s2_layout* layout, const s2_tensors* t, float scale
 static int dense_params(const s2_tensors* t, s2::AttnParams& p) {
   if (t->seqlen % 128 != 0) return S2_ERR_SHAPE;
   p.block_size = s2::kChunk;
-  p.q_tiles.tiles_per_head = t->seqlen / s2::kFwdBM;
-  p.q_tiles.group = s2::kFwdBM / s2::kChunk;
+  p.fwd_tiles.tiles_per_head = (t->seqlen + s2::kFwdBM - 1) / s2::kFwdBM;
+  p.fwd_tiles.group = s2::kFwdBM / s2::kChunk;
+  p.q_tiles.tiles_per_head = t->seqlen / s2::kBwdBM;
+  p.q_tiles.group = s2::kBwdBM / s2::kChunk;
   p.kv_tiles.tiles_per_head = t->seqlen / s2::kBwdBN;
   p.kv_tiles.group = s2::kBwdBN / s2::kChunk;
   return S2_OK;
@@ -239,7 +251,8 @@ int s2_dense_causal_fwd(const s2_tensors* t, float scale, void* stream) {
   s2::AttnParams p = make_params(t, scale);
   st = dense_params(t, p);
   if (st != S2_OK) return st;
-  return hip_ok(s2::launch_fwd(p, true, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
+  if (getenv("S2_FWD_V1")) return hip_ok(s2::launch_fwd(p, true, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
+  return hip_ok(s2::launch_fwd2(p, true, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
 }
 
 int s2_dense_causal_bwd(const s2_tensors* t, float scale, void* workspace, size_t workspace_bytes,
@@ -253,6 +266,7 @@ int s2_dense_causal_bwd(const s2_tensors* t, float scale, void* workspace, size_
   st = dense_params(t, p);
   if (st != S2_OK) return st;
   p.delta = static_cast<float*>(workspace);
+  p.lse2 = p.delta + s2_attn_bwd_workspace_bytes(t->batch, t->heads, t->seqlen, t->head_dim) / 8;
   return hip_ok(s2::launch_bwd(p, true, s2::kBwdAll, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
 }
 

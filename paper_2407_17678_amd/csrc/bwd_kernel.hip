@@ -13,8 +13,9 @@
 // Both main kernels keep the stationary operand's MFMA fragments in registers with the lane
 // owning one stationary row, so the recomputed score tile lands in the C layout with the
 // streamed index in registers; it is then fed back as the B operand of the next contraction
-// without leaving the lane (see device_util.h).  The streamed 64-row chunk is staged through
-// LDS twice: row-major (k = feature) and transposed (k = token).
+// without leaving the lane (see device_util.h).  The streamed 64-row chunk is brought in by
+// direct global -> LDS loads (double buffered) and read in both operand forms from the one
+// row-major tile: row fragments (k = feature) and LDS transpose reads (k = token).
 #include <hip/hip_runtime.h>
 
 #include "config.h"
@@ -50,16 +51,18 @@ __global__ __launch_bounds__(256) void delta_kernel(const AttnParams p) {
   }
 #pragma unroll
   for (int m = LPR / 2; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
-  if (c == 0 && row < rows_total) p.delta[row] = acc;
+  if (c == 0 && row < rows_total) {
+    p.delta[row] = acc;
+    p.lse2[row] = p.lse[row] * kLog2e;  // the main kernels want LSE in base-2 units
+  }
 }
 
 // ------------------------------------------------------------------------------------ dq
 
 template <int D>
 struct DqSmem {
-  uint16_t k[RowTile<D>::kElems];
-  uint16_t v[RowTile<D>::kElems];
-  uint16_t kt[TransposedTile<D>::kElems];
+  uint16_t k[2][DmaTile<D>::kElems];
+  uint16_t v[2][DmaTile<D>::kElems];
 };
 
 template <int D, bool DENSE>
@@ -68,7 +71,8 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
   DqSmem<D>& sm = *reinterpret_cast<DqSmem<D>*>(smem_raw);
 
   const int tid = threadIdx.x;
-  const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63, l32 = lane & 31, half = lane >> 5;
   const int T = p.q_tiles.tiles_per_head;
   int bh, rank;
   if (!map_workgroup(blockIdx.x, p.batch * p.heads, T, bh, rank)) return;
@@ -85,25 +89,6 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
   const int64_t kv_off = b * p.kv_sb + h * p.kv_sh;
   const uint16_t* kb = p.k + kv_off;
   const uint16_t* vb = p.v + kv_off;
-
-  bf16x8 qf[D / 16], gf[D / 16];  // Q^T and dO^T fragments (B operands), lane = query
-  float lse_l = 0.f, delta_l = 0.f;
-#pragma unroll
-  for (int kk = 0; kk < D / 16; ++kk) {
-    if (wave_active) {
-      const int64_t o = q_off + (int64_t)(qw0 + l32) * p.q_st + 16 * kk + 8 * half;
-      qf[kk] = *reinterpret_cast<const bf16x8*>(p.q + o);
-      gf[kk] = *reinterpret_cast<const bf16x8*>(p.d_o + o);
-    } else {
-      qf[kk] = bf16x8{};
-      gf[kk] = bf16x8{};
-    }
-  }
-  if (wave_active) {
-    const int64_t r = ((int64_t)b * p.heads + h) * N + qw0 + l32;
-    lse_l = p.lse[r] * kLog2e;
-    delta_l = p.delta[r];
-  }
 
   int ent_lo = 0, n_ent;
   if (DENSE) {
@@ -124,26 +109,45 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
     }
   };
 
+  const typename DmaTile<D>::Plan plan = DmaTile<D>::plan(p.kv_st, wave, lane);
+  const int trb = DmaTile<D>::tr_base(lane);
+  if (total > 0) {
+    int kv0;
+    bool keep;
+    chunk_of(0, kv0, keep);
+    DmaTile<D>::issue(plan, kb + (int64_t)kv0 * p.kv_st, sm.k[0], wave);
+    DmaTile<D>::issue(plan, vb + (int64_t)kv0 * p.kv_st, sm.v[0], wave);
+  }
+
+  bf16x8 qf[D / 16], gf[D / 16];  // Q^T and dO^T fragments (B operands), lane = query
+  float lse_l = 0.f, delta_l = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < D / 16; ++kk) {
+    if (wave_active) {
+      const int64_t o = q_off + (int64_t)(qw0 + l32) * p.q_st + 16 * kk + 8 * half;
+      qf[kk] = *reinterpret_cast<const bf16x8*>(p.q + o);
+      gf[kk] = *reinterpret_cast<const bf16x8*>(p.d_o + o);
+    } else {
+      qf[kk] = bf16x8{};
+      gf[kk] = bf16x8{};
+    }
+  }
+  if (wave_active) {
+    const int64_t r = ((int64_t)b * p.heads + h) * N + qw0 + l32;
+    lse_l = p.lse2[r];
+    delta_l = p.delta[r];
+  }
+
   f32x16 acc[D / 32];
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt) acc[dt] = f32x16{};
   const float c = p.scale_log2e;
 
-  u32x4 kreg[4];
-  u32x4 vreg[RowTile<D>::kPerThread];
-  if (total > 0) {
-    int kv0;
-    bool keep;
-    chunk_of(0, kv0, keep);
-    TransposedTile<D>::load(kreg, kb + (int64_t)kv0 * p.kv_st, p.kv_st, tid);
-    RowTile<D>::load(vreg, vb + (int64_t)kv0 * p.kv_st, p.kv_st, tid);
-    RowTile<D>::store_quad(kreg, sm.k, tid);
-    TransposedTile<D>::store(kreg, sm.kt, tid);
-    RowTile<D>::store(vreg, sm.v, tid);
-  }
+  wait_all_loads();
   __syncthreads();
 
   for (int it = 0; it < total; ++it) {
+    const int buf = it & 1;
     int kv0;
     bool keep;
     chunk_of(it, kv0, keep);
@@ -151,11 +155,13 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
       int kv1;
       bool keep1;
       chunk_of(it + 1, kv1, keep1);
-      TransposedTile<D>::load(kreg, kb + (int64_t)kv1 * p.kv_st, p.kv_st, tid);
-      RowTile<D>::load(vreg, vb + (int64_t)kv1 * p.kv_st, p.kv_st, tid);
+      DmaTile<D>::issue(plan, kb + (int64_t)kv1 * p.kv_st, sm.k[buf ^ 1], wave);
+      DmaTile<D>::issue(plan, vb + (int64_t)kv1 * p.kv_st, sm.v[buf ^ 1], wave);
     }
 
     if (wave_active && keep && kv0 <= qw0 + 31) {
+      const uint16_t* ks = sm.k[buf];
+      const uint16_t* vs = sm.v[buf];
       const int qpos = qw0 + l32;
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt) {
@@ -163,9 +169,9 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
         if (kbase > qw0 + 31) continue;  // every key of this half-chunk lies after my queries
         f32x16 s = f32x16{}, dp = f32x16{};
 #pragma unroll
-        for (int kk = 0; kk < D / 16; ++kk) s = mfma32(RowTile<D>::frag(sm.k, kt, kk, l32, half), qf[kk], s);
+        for (int kk = 0; kk < D / 16; ++kk) s = mfma32(DmaTile<D>::row_frag(ks, kt, kk, l32, half), qf[kk], s);
 #pragma unroll
-        for (int kk = 0; kk < D / 16; ++kk) dp = mfma32(RowTile<D>::frag(sm.v, kt, kk, l32, half), gf[kk], dp);
+        for (int kk = 0; kk < D / 16; ++kk) dp = mfma32(DmaTile<D>::row_frag(vs, kt, kk, l32, half), gf[kk], dp);
         const bool diag = kbase + 31 > qw0;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -182,17 +188,12 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
                                    s[8 * u + 5], s[8 * u + 6], s[8 * u + 7]);
 #pragma unroll
           for (int dt = 0; dt < D / 32; ++dt)
-            acc[dt] = mfma32(TransposedTile<D>::frag(sm.kt, dt, 2 * kt + u, l32, half), dsb, acc[dt]);
+            acc[dt] = mfma32(DmaTile<D>::tr_frag(ks, dt, 2 * kt + u, trb), dsb, acc[dt]);
         }
       }
     }
 
-    __syncthreads();  // all wavefronts are done reading this chunk
-    if (it + 1 < total) {
-      RowTile<D>::store_quad(kreg, sm.k, tid);
-      TransposedTile<D>::store(kreg, sm.kt, tid);
-      RowTile<D>::store(vreg, sm.v, tid);
-    }
+    wait_all_loads();
     __syncthreads();
   }
 
@@ -213,21 +214,20 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
 
 template <int D>
 struct DkvSmem {
-  uint16_t q[RowTile<D>::kElems];
-  uint16_t g[RowTile<D>::kElems];
-  uint16_t qt[TransposedTile<D>::kElems];
-  uint16_t gt[TransposedTile<D>::kElems];
-  float lse[kChunk];    // already multiplied by log2(e)
-  float delta[kChunk];
+  uint16_t q[2][DmaTile<D>::kElems];
+  uint16_t g[2][DmaTile<D>::kElems];
+  float lse[2][kChunk];    // base-2 units
+  float delta[2][kChunk];
 };
 
 template <int D, bool DENSE>
-__global__ __launch_bounds__(kThreads, 1) void dkdv_kernel(const AttnParams p) {
+__global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   DkvSmem<D>& sm = *reinterpret_cast<DkvSmem<D>*>(smem_raw);
 
   const int tid = threadIdx.x;
-  const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63, l32 = lane & 31, half = lane >> 5;
   const int T = p.kv_tiles.tiles_per_head;
   int bh, rank;
   if (!map_workgroup(blockIdx.x, p.batch * p.heads, T, bh, rank)) return;
@@ -254,21 +254,8 @@ __global__ __launch_bounds__(kThreads, 1) void dkdv_kernel(const AttnParams p) {
   const int64_t kv_off = b * p.kv_sb + h * p.kv_sh;
   const uint16_t* qb = p.q + q_off;
   const uint16_t* gb = p.d_o + q_off;
-  const float* lse_b = p.lse + ((int64_t)b * p.heads + h) * N;
+  const float* lse_b = p.lse2 + ((int64_t)b * p.heads + h) * N;
   const float* delta_b = p.delta + ((int64_t)b * p.heads + h) * N;
-
-  bf16x8 kf[D / 16], vf[D / 16];  // K and V fragments (B operands), lane = key
-#pragma unroll
-  for (int kk = 0; kk < D / 16; ++kk) {
-    if (wave_active) {
-      const int64_t o = kv_off + (int64_t)(kvw0 + l32) * p.kv_st + 16 * kk + 8 * half;
-      kf[kk] = *reinterpret_cast<const bf16x8*>(p.k + o);
-      vf[kk] = *reinterpret_cast<const bf16x8*>(p.v + o);
-    } else {
-      kf[kk] = bf16x8{};
-      vf[kk] = bf16x8{};
-    }
-  }
 
   int ent_lo = 0, n_ent;
   if (DENSE) {
@@ -289,6 +276,37 @@ __global__ __launch_bounds__(kThreads, 1) void dkdv_kernel(const AttnParams p) {
     }
   };
 
+  const typename DmaTile<D>::Plan plan = DmaTile<D>::plan(p.q_st, wave, lane);
+  const int trb = DmaTile<D>::tr_base(lane);
+  typedef const __attribute__((address_space(1))) void* gptr;
+  typedef __attribute__((address_space(3))) void* lptr;
+  auto issue_chunk = [&](int q0, int buf) {
+    DmaTile<D>::issue(plan, qb + (int64_t)q0 * p.q_st, sm.q[buf], wave);
+    DmaTile<D>::issue(plan, gb + (int64_t)q0 * p.q_st, sm.g[buf], wave);
+    // 64 floats each: one 4-byte direct load per lane
+    if (wave == 0) __builtin_amdgcn_global_load_lds((gptr)(lse_b + q0 + lane), (lptr)sm.lse[buf], 4, 0, 0);
+    if (wave == 1) __builtin_amdgcn_global_load_lds((gptr)(delta_b + q0 + lane), (lptr)sm.delta[buf], 4, 0, 0);
+  };
+  if (total > 0) {
+    int q0;
+    bool keep;
+    chunk_of(0, q0, keep);
+    issue_chunk(q0, 0);
+  }
+
+  bf16x8 kf[D / 16], vf[D / 16];  // K and V fragments (B operands), lane = key
+#pragma unroll
+  for (int kk = 0; kk < D / 16; ++kk) {
+    if (wave_active) {
+      const int64_t o = kv_off + (int64_t)(kvw0 + l32) * p.kv_st + 16 * kk + 8 * half;
+      kf[kk] = *reinterpret_cast<const bf16x8*>(p.k + o);
+      vf[kk] = *reinterpret_cast<const bf16x8*>(p.v + o);
+    } else {
+      kf[kk] = bf16x8{};
+      vf[kk] = bf16x8{};
+    }
+  }
+
   f32x16 acc_dk[D / 32], acc_dv[D / 32];
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt) {
@@ -297,33 +315,11 @@ __global__ __launch_bounds__(kThreads, 1) void dkdv_kernel(const AttnParams p) {
   }
   const float c = p.scale_log2e;
 
-  u32x4 qreg[4], greg[4];
-  float stat = 0.f;  // threads 0..63 carry lse, 64..127 carry delta
-  auto load_chunk = [&](int q0) {
-    TransposedTile<D>::load(qreg, qb + (int64_t)q0 * p.q_st, p.q_st, tid);
-    TransposedTile<D>::load(greg, gb + (int64_t)q0 * p.q_st, p.q_st, tid);
-    if (tid < 64) stat = lse_b[q0 + tid] * kLog2e;
-    else if (tid < 128) stat = delta_b[q0 + tid - 64];
-  };
-  auto store_chunk = [&]() {
-    RowTile<D>::store_quad(qreg, sm.q, tid);
-    TransposedTile<D>::store(qreg, sm.qt, tid);
-    RowTile<D>::store_quad(greg, sm.g, tid);
-    TransposedTile<D>::store(greg, sm.gt, tid);
-    if (tid < 64) sm.lse[tid] = stat;
-    else if (tid < 128) sm.delta[tid - 64] = stat;
-  };
-
-  if (total > 0) {
-    int q0;
-    bool keep;
-    chunk_of(0, q0, keep);
-    load_chunk(q0);
-    store_chunk();
-  }
+  wait_all_loads();
   __syncthreads();
 
   for (int it = 0; it < total; ++it) {
+    const int buf = it & 1;
     int q0;
     bool keep;
     chunk_of(it, q0, keep);
@@ -331,10 +327,12 @@ __global__ __launch_bounds__(kThreads, 1) void dkdv_kernel(const AttnParams p) {
       int q1;
       bool keep1;
       chunk_of(it + 1, q1, keep1);
-      load_chunk(q1);
+      issue_chunk(q1, buf ^ 1);
     }
 
     if (wave_active && keep && q0 + kChunk - 1 >= kvw0) {
+      const uint16_t* qs = sm.q[buf];
+      const uint16_t* gs = sm.g[buf];
       const int key = kvw0 + l32;
 #pragma unroll
       for (int qt = 0; qt < 2; ++qt) {
@@ -342,15 +340,15 @@ __global__ __launch_bounds__(kThreads, 1) void dkdv_kernel(const AttnParams p) {
         if (qbase + 31 < kvw0) continue;  // every query of this half-chunk lies before my keys
         f32x16 s = f32x16{}, dp = f32x16{};
 #pragma unroll
-        for (int kk = 0; kk < D / 16; ++kk) s = mfma32(RowTile<D>::frag(sm.q, qt, kk, l32, half), kf[kk], s);
+        for (int kk = 0; kk < D / 16; ++kk) s = mfma32(DmaTile<D>::row_frag(qs, qt, kk, l32, half), kf[kk], s);
 #pragma unroll
-        for (int kk = 0; kk < D / 16; ++kk) dp = mfma32(RowTile<D>::frag(sm.g, qt, kk, l32, half), vf[kk], dp);
+        for (int kk = 0; kk < D / 16; ++kk) dp = mfma32(DmaTile<D>::row_frag(gs, qt, kk, l32, half), vf[kk], dp);
         const bool diag = qbase < kvw0 + 31;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const int r0 = 32 * qt + 8 * g + 4 * half;
-          const f32x4 l4 = *reinterpret_cast<const f32x4*>(&sm.lse[r0]);
-          const f32x4 d4 = *reinterpret_cast<const f32x4*>(&sm.delta[r0]);
+          const f32x4 l4 = *reinterpret_cast<const f32x4*>(&sm.lse[buf][r0]);
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(&sm.delta[buf][r0]);
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int r = 4 * g + e;
@@ -368,15 +366,14 @@ __global__ __launch_bounds__(kThreads, 1) void dkdv_kernel(const AttnParams p) {
                                    dp[8 * u + 5], dp[8 * u + 6], dp[8 * u + 7]);
 #pragma unroll
           for (int dt = 0; dt < D / 32; ++dt) {
-            acc_dv[dt] = mfma32(TransposedTile<D>::frag(sm.gt, dt, 2 * qt + u, l32, half), pb, acc_dv[dt]);
-            acc_dk[dt] = mfma32(TransposedTile<D>::frag(sm.qt, dt, 2 * qt + u, l32, half), dsb, acc_dk[dt]);
+            acc_dv[dt] = mfma32(DmaTile<D>::tr_frag(gs, dt, 2 * qt + u, trb), pb, acc_dv[dt]);
+            acc_dk[dt] = mfma32(DmaTile<D>::tr_frag(qs, dt, 2 * qt + u, trb), dsb, acc_dk[dt]);
           }
         }
       }
     }
 
-    __syncthreads();
-    if (it + 1 < total) store_chunk();
+    wait_all_loads();
     __syncthreads();
   }
 

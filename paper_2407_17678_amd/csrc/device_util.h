@@ -95,6 +95,9 @@ struct RowTile {
 // elements (36 dwords).  Inside each run of 16 tokens the column order is permuted so that one
 // 16-byte read gives a lane the eight tokens its half contracts over when the other operand is
 // a C-layout tile: column 16*slab + 8*half + e holds token 16*slab + 8*(e/4) + 4*half + e%4.
+// On top of that, rows whose index has bit 4 set swap their two 32-token halves (column ^ 32):
+// the 8-byte transposed stores of one wavefront go to rows 8c+e for four values of c, 8 rows are
+// 32 banks apart, and without the swap c and c+2 would land on the same banks.
 // Read as an MFMA A fragment whose 32-side is the feature and whose k is the token axis.
 // ---------------------------------------------------------------------------------------------
 template <int D>
@@ -119,7 +122,8 @@ struct TransposedTile {
   __device__ static __forceinline__ void store(const u32x4 (&r)[4], uint16_t* tile, int tid) {
     if (!mine(tid)) return;
     const int c = chunk_of(tid), a = group_of(tid);
-    const int col = 16 * (a >> 2) + 8 * (a & 1) + 4 * ((a & 3) >> 1);
+    // rows 8c..8c+7 share bit 4 of the row index (c >> 1): the column swizzle below
+    const int col = (16 * (a >> 2) + 8 * (a & 1) + 4 * ((a & 3) >> 1)) ^ (32 * ((c >> 1) & 1));
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
       // dword m of each source row holds features 2m (low half) and 2m+1 (high half)
@@ -134,9 +138,97 @@ struct TransposedTile {
   }
   // fragment: feature row = 32*ft + lane%32, token slab (16 tokens), this lane's half
   __device__ static __forceinline__ bf16x8 frag(const uint16_t* tile, int ft, int slab, int l32, int half) {
-    return *reinterpret_cast<const bf16x8*>(tile + (32 * ft + l32) * kStride + 16 * slab + 8 * half);
+    const int col = (16 * slab + 8 * half) ^ (32 * ((l32 >> 4) & 1));
+    return *reinterpret_cast<const bf16x8*>(tile + (32 * ft + l32) * kStride + col);
   }
 };
+
+// ---------------------------------------------------------------------------------------------
+// DmaTile: a 64-row x D bf16 chunk kept row-major in LDS and filled by direct global -> LDS loads
+// (global_load_lds_dwordx4: no staging registers, no LDS store instructions).  Both operand
+// forms are read from this one tile: row fragments with 16-byte reads (k = feature) and
+// transposed fragments with the LDS transpose read ds_read_b64_tr_b16 (k = token).
+//
+// Row stride is 76 dwords for D = 128 and 52 dwords for D = 64: measured on gfx950, these are
+// strides at which both the 16-byte row reads (32 consecutive rows, the two wavefront halves 16
+// bytes apart) and the transpose reads (groups of 16 lanes covering 4 rows x 32 bytes) run at the
+// conflict-free rate.  Both tile sizes are whole multiples of the 1024 bytes one wavefront-wide
+// direct load fills.
+//
+// Direct loads write LDS at (wave-uniform base) + 16 * lane, so LDS position decides which global
+// address a lane fetches: position p holds row p / stride, 16-byte piece (p % stride) / 16; the
+// pad pieces at the end of each row fetch piece 0 of the same row (in bounds, never read).
+//
+// ds_read_b64_tr_b16, within each group of 16 lanes: lane 4e+q supplies the address of 4
+// consecutive bf16 (row e of a 4 x 16 block, piece q); lane i receives element i of rows 0..3.
+// So a group pointed at tokens t..t+3, features f..f+15 hands lane i the four tokens of feature
+// f+i: exactly the k-order of half a C-layout B operand (see the top of this file).
+// ---------------------------------------------------------------------------------------------
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+template <int D>
+struct DmaTile {
+  static constexpr int kStride = (D == 128) ? 152 : 104;  // elements
+  static constexpr int kElems = 64 * kStride;
+  static constexpr int kBytes = kElems * 2;
+  static constexpr int kInstr = kBytes / 1024;            // wavefront-wide loads per tile
+  static constexpr int kPerWave = (kInstr + 3) / 4;
+  static_assert(kBytes % 1024 == 0, "tile must be a whole number of wavefront loads");
+
+  struct Plan {
+    int32_t goff[kPerWave];  // element offset from the chunk's first row, per load of this lane
+  };
+
+  __device__ static __forceinline__ Plan plan(int64_t row_stride, int wave, int lane) {
+    Plan pl;
+#pragma unroll
+    for (int n = 0; n < kPerWave; ++n) {
+      const int pos = (4 * n + wave) * 1024 + lane * 16;
+      const int row = pos / (kStride * 2);
+      int piece = (pos - row * kStride * 2) / 16;
+      if (piece >= D / 8) piece = 0;
+      pl.goff[n] = (int32_t)(min(row, 63) * row_stride) + 8 * piece;
+    }
+    return pl;
+  }
+
+  // Starts the loads of one chunk; they are complete after s_waitcnt vmcnt(0).
+  __device__ static __forceinline__ void issue(const Plan& pl, const uint16_t* gbase, uint16_t* tile,
+                                               int wave) {
+#pragma unroll
+    for (int n = 0; n < kPerWave; ++n) {
+      const int instr = 4 * n + wave;
+      if (instr < kInstr)
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void*)(gbase + pl.goff[n]),
+            (__attribute__((address_space(3))) void*)(tile + instr * 512), 16, 0, 0);
+    }
+  }
+
+  // row fragment: row = 32*rt + lane%32, features 16*kk + 8*half .. +7
+  __device__ static __forceinline__ bf16x8 row_frag(const uint16_t* tile, int rt, int kk, int l32, int half) {
+    return *reinterpret_cast<const bf16x8*>(tile + (32 * rt + l32) * kStride + 16 * kk + 8 * half);
+  }
+
+  // lane-dependent part of a transposed fragment's address (elements)
+  __device__ static __forceinline__ int tr_base(int lane) {
+    const int g = lane >> 4, e = (lane & 15) >> 2, q = lane & 3;
+    return (4 * (g >> 1) + e) * kStride + 16 * (g & 1) + 4 * q;
+  }
+  // transposed fragment: features 32*ft + lane%32, the 16 tokens of `slab` in C-layout k order
+  __device__ static __forceinline__ bf16x8 tr_frag(const uint16_t* tile, int ft, int slab, int trb) {
+    typedef __attribute__((address_space(3))) s16x4* lds_ptr;
+    const uint16_t* p = tile + trb + 16 * slab * kStride + 32 * ft;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 8 * kStride));
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, both);
+  }
+};
+
+// Everything outstanding (direct loads included) has landed.
+__device__ __forceinline__ void wait_all_loads() { __builtin_amdgcn_s_waitcnt(0); }
 
 // Workgroup index -> (batch*head, rank inside the head) such that all tiles of one (batch, head)
 // run on one XCD.  Workgroups are handed to the 8 XCDs round-robin by linear index, and each XCD

@@ -27,13 +27,15 @@ struct AttnParams {
   uint16_t* dk;
   uint16_t* dv;
   float* delta;  // workspace: rowsum(dO * O), [batch, heads, seqlen]
+  float* lse2;   // workspace: lse * log2(e), [batch, heads, seqlen]
   int batch, heads, seqlen, head_dim;
   int64_t q_sb, q_sh, q_st;
   int64_t kv_sb, kv_sh, kv_st;
   float scale;        // softmax scale
   float scale_log2e;  // scale * log2(e)
   int block_size;     // S (sparse path); 64 on the dense path
-  DevTiles q_tiles;   // row tiles -> KV blocks
+  DevTiles fwd_tiles; // row tiles of the forward kernel -> KV blocks
+  DevTiles q_tiles;   // row tiles of the dQ kernel -> KV blocks
   DevTiles kv_tiles;  // column tiles -> Q blocks
 };
 
@@ -54,6 +56,7 @@ struct DecodeParams {
 
 // Each returns the hipError_t of the launch (hipGetLastError after the launch).
 hipError_t launch_fwd(const AttnParams& p, bool dense, hipStream_t stream);
+hipError_t launch_fwd2(const AttnParams& p, bool dense, hipStream_t stream);
 // `stages` selects which of the three backward launches run: 1 = delta, 2 = dK/dV, 4 = dQ.
 constexpr int kBwdDelta = 1, kBwdDkDv = 2, kBwdDq = 4, kBwdAll = 7;
 hipError_t launch_bwd(const AttnParams& p, bool dense, int stages, hipStream_t stream);

@@ -38,7 +38,8 @@ struct s2_layout {
   int covers_all = 0;
   bool on_device = false;
   int device = -1;
-  s2::TileList q_tiles;   // row groups  -> kept KV blocks   (forward, dQ pass)
+  s2::TileList fwd_tiles; // row groups  -> kept KV blocks   (forward)
+  s2::TileList q_tiles;   // row groups  -> kept KV blocks   (dQ pass)
   s2::TileList kv_tiles;  // column groups -> attending Q blocks (dK/dV pass)
 };
 
