@@ -3,7 +3,6 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
-#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -71,6 +70,8 @@ int check_tensors(const s2_tensors* t, bool need_bwd, float scale) {
   for (int64_t s : strides)
     if (s < 0 || (s & 7) != 0) return S2_ERR_ALIGN;
   if (t->q_stride_t < t->head_dim || t->kv_stride_t < t->head_dim) return S2_ERR_ALIGN;
+  // the kernels address the 64 rows of a chunk with 32-bit element offsets
+  if (t->q_stride_t > (1 << 24) || t->kv_stride_t > (1 << 24)) return S2_ERR_SHAPE;
   const void* ptrs[9] = {t->q, t->k, t->v, t->o, t->lse, t->d_o, t->dq, t->dk, t->dv};
   for (int i = 0; i < (need_bwd ? 9 : 5); ++i)
     if (!aligned16(ptrs[i])) return S2_ERR_ALIGN;
@@ -194,8 +195,7 @@ int s2_attn_fwd(const s2_layout* layout, const s2_tensors* t, float scale, void*
   p.fwd_tiles = dev_tiles(layout->fwd_tiles);
   p.q_tiles = dev_tiles(layout->q_tiles);
   p.kv_tiles = dev_tiles(layout->kv_tiles);
-  if (getenv("S2_FWD_V1")) return hip_ok(s2::launch_fwd(p, false, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
-  return hip_ok(s2::launch_fwd2(p, false, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
+  return hip_ok(s2::launch_fwd(p, false, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
 }
 
 size_t s2_attn_bwd_workspace_bytes(int32_t batch, int32_t heads, int32_t seqlen, int32_t head_dim) {
@@ -251,8 +251,7 @@ int s2_dense_causal_fwd(const s2_tensors* t, float scale, void* stream) {
   s2::AttnParams p = make_params(t, scale);
   st = dense_params(t, p);
   if (st != S2_OK) return st;
-  if (getenv("S2_FWD_V1")) return hip_ok(s2::launch_fwd(p, true, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
-  return hip_ok(s2::launch_fwd2(p, true, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
+  return hip_ok(s2::launch_fwd(p, true, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
 }
 
 int s2_dense_causal_bwd(const s2_tensors* t, float scale, void* workspace, size_t workspace_bytes,

@@ -230,7 +230,7 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
   const int lane = tid & 63, l32 = lane & 31, half = lane >> 5;
   const int T = p.kv_tiles.tiles_per_head;
   int bh, rank;
-  if (!map_workgroup(blockIdx.x, p.batch * p.heads, T, bh, rank)) return;
+  if (!map_workgroup_interleaved(blockIdx.x, p.batch * p.heads, T, bh, rank)) return;
   const int b = bh / p.heads, h = bh - b * p.heads;
   const int tile = DENSE ? rank : p.kv_tiles.order[h * T + rank];  // dense: first key tiles are longest
   const int S = DENSE ? kChunk : p.block_size;
@@ -278,14 +278,12 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
 
   const typename DmaTile<D>::Plan plan = DmaTile<D>::plan(p.q_st, wave, lane);
   const int trb = DmaTile<D>::tr_base(lane);
-  typedef const __attribute__((address_space(1))) void* gptr;
-  typedef __attribute__((address_space(3))) void* lptr;
   auto issue_chunk = [&](int q0, int buf) {
     DmaTile<D>::issue(plan, qb + (int64_t)q0 * p.q_st, sm.q[buf], wave);
     DmaTile<D>::issue(plan, gb + (int64_t)q0 * p.q_st, sm.g[buf], wave);
     // 64 floats each: one 4-byte direct load per lane
-    if (wave == 0) __builtin_amdgcn_global_load_lds((gptr)(lse_b + q0 + lane), (lptr)sm.lse[buf], 4, 0, 0);
-    if (wave == 1) __builtin_amdgcn_global_load_lds((gptr)(delta_b + q0 + lane), (lptr)sm.delta[buf], 4, 0, 0);
+    if (wave == 0) dma4(lse_b + q0 + lane, lds_addr(sm.lse[buf]));
+    if (wave == 1) dma4(delta_b + q0 + lane, lds_addr(sm.delta[buf]));
   };
   if (total > 0) {
     int q0;

@@ -1,6 +1,6 @@
-// Internal device-side helpers for the gfx950 kernels: MFMA fragment types, the LDS tile layouts,
-// and the global -> register -> LDS staging of a 64-row bf16 chunk, both row-major and
-// transposed.
+// Internal device-side helpers for the gfx950 kernels: MFMA fragment types, the LDS tile that a
+// 64-row bf16 chunk is staged in (direct global -> LDS loads, row and transposed fragment reads),
+// and the workgroup -> tile mappings.
 //
 // Fragment conventions of v_mfma_f32_32x32x16_bf16 (D = A x B + C, 64 lanes, half = lane / 32):
 //   A (32 x 16): lane holds row (lane % 32), the 8 k-values of its half.
@@ -10,8 +10,8 @@
 // The contraction index may be permuted freely as long as A and B agree, which is what lets a
 // C-layout tile be fed back as a B operand without moving data between lanes: registers
 // 8u..8u+7 of a C tile are, for the lane's half, the rows {16u + 4*half + 0..3,
-// 16u + 8 + 4*half + 0..3}; the matching A operand is stored in LDS in exactly that order
-// (see TransposedTile).
+// 16u + 8 + 4*half + 0..3}; the matching A operand is fetched from LDS in exactly that order
+// (see DmaTile::tr_frag).
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -45,105 +45,6 @@ __device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3, 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Row-major LDS tile: 64 rows x D bf16, row stride D+8 elements.  (D+8)*2 bytes = 68 or 36
-// dwords per row, so the 16 lanes of a b128 access that differ in row hit disjoint banks.
-// Read as an MFMA A/B fragment whose 32-side is the tile row and whose k is the D axis.
-// ---------------------------------------------------------------------------------------------
-template <int D>
-struct RowTile {
-  static constexpr int kStride = D + 8;           // elements
-  static constexpr int kElems = 64 * kStride;     // per tile
-  static constexpr int kPieces = 64 * D / 8;      // 16-byte pieces
-  static constexpr int kPerThread = kPieces / 256;
-
-  // global -> registers (coalesced: consecutive threads take consecutive 16 bytes of a row)
-  __device__ static __forceinline__ void load(u32x4 (&r)[kPerThread], const uint16_t* base,
-                                              int64_t row_stride, int tid) {
-#pragma unroll
-    for (int n = 0; n < kPerThread; ++n) {
-      const int p = tid + 256 * n;
-      const int row = p / (D / 8), c = p % (D / 8);
-      r[n] = *reinterpret_cast<const u32x4*>(base + (int64_t)row * row_stride + 8 * c);
-    }
-  }
-  // registers -> LDS
-  __device__ static __forceinline__ void store(const u32x4 (&r)[kPerThread], uint16_t* tile, int tid) {
-#pragma unroll
-    for (int n = 0; n < kPerThread; ++n) {
-      const int p = tid + 256 * n;
-      const int row = p / (D / 8), c = p % (D / 8);
-      *reinterpret_cast<u32x4*>(tile + row * kStride + 8 * c) = r[n];
-    }
-  }
-  // registers -> LDS when the chunk was loaded with TransposedTile's thread mapping (thread holds
-  // rows 4a..4a+3, features 8c..8c+7), so one global load can feed both tile forms
-  __device__ static __forceinline__ void store_quad(const u32x4 (&r)[4], uint16_t* tile, int tid) {
-    if (tid >= 16 * (D / 8)) return;
-    const int c = (tid & 3) + 4 * (tid >> 6), a = (tid >> 2) & 15;
-#pragma unroll
-    for (int n = 0; n < 4; ++n)
-      *reinterpret_cast<u32x4*>(tile + (4 * a + n) * kStride + 8 * c) = r[n];
-  }
-  // fragment: row = 32*rt + lane%32, k-slab kk (16 values of D), this lane's half
-  __device__ static __forceinline__ bf16x8 frag(const uint16_t* tile, int rt, int kk, int l32, int half) {
-    return *reinterpret_cast<const bf16x8*>(tile + (32 * rt + l32) * kStride + 16 * kk + 8 * half);
-  }
-};
-
-// ---------------------------------------------------------------------------------------------
-// Transposed LDS tile: D rows (one per feature) x 64 columns (the chunk's tokens), row stride 72
-// elements (36 dwords).  Inside each run of 16 tokens the column order is permuted so that one
-// 16-byte read gives a lane the eight tokens its half contracts over when the other operand is
-// a C-layout tile: column 16*slab + 8*half + e holds token 16*slab + 8*(e/4) + 4*half + e%4.
-// On top of that, rows whose index has bit 4 set swap their two 32-token halves (column ^ 32):
-// the 8-byte transposed stores of one wavefront go to rows 8c+e for four values of c, 8 rows are
-// 32 banks apart, and without the swap c and c+2 would land on the same banks.
-// Read as an MFMA A fragment whose 32-side is the feature and whose k is the token axis.
-// ---------------------------------------------------------------------------------------------
-template <int D>
-struct TransposedTile {
-  static constexpr int kStride = 72;
-  static constexpr int kElems = D * kStride;
-  static constexpr int kChunks = D / 8;  // 8-feature chunks per row of the source
-
-  // thread -> (token group a of 4 rows, feature chunk c); threads beyond 16*kChunks idle
-  __device__ static __forceinline__ bool mine(int tid) { return tid < 16 * kChunks; }
-  __device__ static __forceinline__ int chunk_of(int tid) { return (tid & 3) + 4 * (tid >> 6); }
-  __device__ static __forceinline__ int group_of(int tid) { return (tid >> 2) & 15; }
-
-  __device__ static __forceinline__ void load(u32x4 (&r)[4], const uint16_t* base, int64_t row_stride,
-                                              int tid) {
-    if (!mine(tid)) return;
-    const int c = chunk_of(tid), a = group_of(tid);
-#pragma unroll
-    for (int n = 0; n < 4; ++n)
-      r[n] = *reinterpret_cast<const u32x4*>(base + (int64_t)(4 * a + n) * row_stride + 8 * c);
-  }
-  __device__ static __forceinline__ void store(const u32x4 (&r)[4], uint16_t* tile, int tid) {
-    if (!mine(tid)) return;
-    const int c = chunk_of(tid), a = group_of(tid);
-    // rows 8c..8c+7 share bit 4 of the row index (c >> 1): the column swizzle below
-    const int col = (16 * (a >> 2) + 8 * (a & 1) + 4 * ((a & 3) >> 1)) ^ (32 * ((c >> 1) & 1));
-#pragma unroll
-    for (int m = 0; m < 4; ++m) {
-      // dword m of each source row holds features 2m (low half) and 2m+1 (high half)
-      u32x2 even, odd;
-      even[0] = __builtin_amdgcn_perm(r[1][m], r[0][m], 0x05040100u);
-      even[1] = __builtin_amdgcn_perm(r[3][m], r[2][m], 0x05040100u);
-      odd[0] = __builtin_amdgcn_perm(r[1][m], r[0][m], 0x07060302u);
-      odd[1] = __builtin_amdgcn_perm(r[3][m], r[2][m], 0x07060302u);
-      *reinterpret_cast<u32x2*>(tile + (8 * c + 2 * m) * kStride + col) = even;
-      *reinterpret_cast<u32x2*>(tile + (8 * c + 2 * m + 1) * kStride + col) = odd;
-    }
-  }
-  // fragment: feature row = 32*ft + lane%32, token slab (16 tokens), this lane's half
-  __device__ static __forceinline__ bf16x8 frag(const uint16_t* tile, int ft, int slab, int l32, int half) {
-    const int col = (16 * slab + 8 * half) ^ (32 * ((l32 >> 4) & 1));
-    return *reinterpret_cast<const bf16x8*>(tile + (32 * ft + l32) * kStride + col);
-  }
-};
-
-// ---------------------------------------------------------------------------------------------
 // DmaTile: a 64-row x D bf16 chunk kept row-major in LDS and filled by direct global -> LDS loads
 // (global_load_lds_dwordx4: no staging registers, no LDS store instructions).  Both operand
 // forms are read from this one tile: row fragments with 16-byte reads (k = feature) and
@@ -165,6 +66,24 @@ struct TransposedTile {
 // f+i: exactly the k-order of half a C-layout B operand (see the top of this file).
 // ---------------------------------------------------------------------------------------------
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+// Byte address inside LDS of a pointer to __shared__ memory.
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
+}
+
+// One wavefront-wide direct load: lane i fetches `bytes` (16 or 4) from its own global address
+// into LDS at lds_base + bytes * i.  lds_base must be wave-uniform (it goes through M0).
+// Written as inline assembly on purpose: the compiler then does not track these loads and so does
+// not make unrelated LDS reads wait for a prefetch in flight; the kernels wait for them explicitly
+// (wait_all_loads) before the barrier that publishes a stage.  Untracked loads only make the
+// compiler's own vmcnt waits more conservative, never less (the counter retires in order).
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
+}
+__device__ __forceinline__ void dma4(const void* gptr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
+}
 
 template <int D>
 struct DmaTile {
@@ -193,15 +112,13 @@ struct DmaTile {
   }
 
   // Starts the loads of one chunk; they are complete after s_waitcnt vmcnt(0).
-  __device__ static __forceinline__ void issue(const Plan& pl, const uint16_t* gbase, uint16_t* tile,
+  __device__ static __forceinline__ void issue(const Plan& pl, const uint16_t* gbase, const uint16_t* tile,
                                                int wave) {
+    const uint32_t base = lds_addr(tile);
 #pragma unroll
     for (int n = 0; n < kPerWave; ++n) {
       const int instr = 4 * n + wave;
-      if (instr < kInstr)
-        __builtin_amdgcn_global_load_lds(
-            (const __attribute__((address_space(1))) void*)(gbase + pl.goff[n]),
-            (__attribute__((address_space(3))) void*)(tile + instr * 512), 16, 0, 0);
+      if (instr < kInstr) dma16(gbase + pl.goff[n], base + instr * 1024);
     }
   }
 
@@ -228,7 +145,7 @@ struct DmaTile {
 };
 
 // Everything outstanding (direct loads included) has landed.
-__device__ __forceinline__ void wait_all_loads() { __builtin_amdgcn_s_waitcnt(0); }
+__device__ __forceinline__ void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory"); }
 
 // Workgroup index -> (batch*head, rank inside the head) such that all tiles of one (batch, head)
 // run on one XCD.  Workgroups are handed to the 8 XCDs round-robin by linear index, and each XCD
@@ -239,6 +156,18 @@ __device__ __forceinline__ bool map_workgroup(int wg, int bh_total, int tiles, i
   const int k = slot / tiles;
   rank = slot - k * tiles;
   bh = x + 8 * k;
+  return bh < bh_total;
+}
+// Same XCD assignment, but the (batch, head) pairs of an XCD are interleaved: all their longest
+// tiles are dispatched first, then all their second longest, ...  Used where tile lengths are very
+// uneven (key tiles on a stripe are attended by hundreds of query blocks, the others by a few), so
+// that the longest tile of the last head does not start late and become the tail of the launch.
+__device__ __forceinline__ bool map_workgroup_interleaved(int wg, int bh_total, int tiles, int& bh,
+                                                          int& rank) {
+  const int x = wg & 7, slot = wg >> 3;
+  const int per_xcd = (bh_total + 7) >> 3;  // slots are laid out for the fullest XCD
+  rank = slot / per_xcd;
+  bh = x + 8 * (slot - rank * per_xcd);
   return bh < bh_total;
 }
 __host__ __device__ inline int grid_for(int bh_total, int tiles) { return 8 * ((bh_total + 7) / 8) * tiles; }

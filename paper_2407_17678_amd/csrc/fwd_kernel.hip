@@ -1,14 +1,17 @@
 // Forward kernel: block-sparse causal attention with per-head lists of kept KV blocks
 // (section 3.2: iterate K/V tiles through on-chip memory, softmax over the kept keys only;
-// section 4.2: which blocks a head keeps).  One workgroup owns a 128-row query tile that spans
-// one or two mask rows (the Merge-Q idea of section 3.2: a big tile, a fine mask); it walks the
-// merged list of KV blocks any of its rows keeps, and each wavefront skips the blocks its own
+// section 4.2: which blocks a head keeps).  One workgroup owns a query tile of 128*QT rows that
+// spans several mask rows (the Merge-Q idea of section 3.2: a big tile, a fine mask); it walks
+// the merged list of KV blocks any of its rows keeps, and each wavefront skips the blocks its own
 // mask row does not keep.
 //
 // Orientation: the score tile is computed transposed, S^T = K Q^T, so that a lane owns one
 // query (one column of the C layout).  Row max / row sum are then in-lane reductions plus one
-// exchange with the other half of the wavefront, and the probabilities can be fed to the second
+// exchange with the other half of the wavefront, and the probabilities feed the second
 // contraction O^T += V^T P^T straight from the accumulator registers.
+//
+// K and V chunks (64 keys) are brought in by direct global -> LDS loads, double buffered; K is
+// read as row fragments, V through the LDS transpose read (DmaTile in device_util.h).
 #include <hip/hip_runtime.h>
 
 #include "config.h"
@@ -21,52 +24,53 @@ namespace {
 
 constexpr float kNegInf = -__builtin_inff();
 
-template <int D>
-struct FwdSmem {
-  uint16_t k[2][RowTile<D>::kElems];
-  uint16_t vt[2][TransposedTile<D>::kElems];
-};
 
-template <int D, bool DENSE>
-__global__ __launch_bounds__(kThreads, 2) void fwd_kernel(const AttnParams p) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  FwdSmem<D>& sm = *reinterpret_cast<FwdSmem<D>*>(smem_raw);
+template <int D, bool DENSE, int QT>
+__global__ __launch_bounds__(kThreads, (QT == 1 ? 2 : 1)) void fwd_kernel(const AttnParams p) {
+  __shared__ __attribute__((aligned(16))) uint16_t sk[2][DmaTile<D>::kElems];
+  __shared__ __attribute__((aligned(16))) uint16_t sv[2][DmaTile<D>::kElems];
+  constexpr int BM = 128 * QT;
+  constexpr int MW = 32 * QT;  // rows per wavefront
 
   const int tid = threadIdx.x;
-  const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
-  const int T = p.q_tiles.tiles_per_head;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+  const int T = p.fwd_tiles.tiles_per_head;
   int bh, rank;
   if (!map_workgroup(blockIdx.x, p.batch * p.heads, T, bh, rank)) return;
   const int b = bh / p.heads, h = bh - b * p.heads;
-  const int tile = DENSE ? (T - 1 - rank) : p.q_tiles.order[h * T + rank];
+  const int tile = DENSE ? (T - 1 - rank) : p.fwd_tiles.order[h * T + rank];
   const int S = DENSE ? kChunk : p.block_size;
   const int cpb = S / kChunk;  // 64-key chunks per mask block
 
   const int N = p.seqlen;
-  const int qw0 = tile * kFwdBM + wave * 32;  // first query row of this wavefront
+  const int qw0 = tile * BM + wave * MW;  // first query row of this wavefront
   const bool wave_active = qw0 < N;
-  const int my_member = (qw0 / S) - tile * (kFwdBM / S);  // which mask row of the tile I am in
+  const int my_member = (qw0 / S) - tile * (BM / S);  // which mask row of the tile I am in
 
   const uint16_t* qb = p.q + b * p.q_sb + h * p.q_sh;
   const uint16_t* kb = p.k + b * p.kv_sb + h * p.kv_sh;
   const uint16_t* vb = p.v + b * p.kv_sb + h * p.kv_sh;
 
   // Q^T fragments stay in registers for the whole tile.
-  bf16x8 qf[D / 16];
+  bf16x8 qf[QT][D / 16];
 #pragma unroll
-  for (int kk = 0; kk < D / 16; ++kk) {
-    if (wave_active)
-      qf[kk] = *reinterpret_cast<const bf16x8*>(qb + (int64_t)(qw0 + l32) * p.q_st + 16 * kk + 8 * half);
-    else
-      qf[kk] = bf16x8{};
-  }
+  for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) {
+      if (wave_active)
+        qf[qt][kk] = *reinterpret_cast<const bf16x8*>(qb + (int64_t)(qw0 + 32 * qt + l32) * p.q_st + 16 * kk +
+                                                      8 * half);
+      else
+        qf[qt][kk] = bf16x8{};
+    }
 
   int ent_lo = 0, n_ent;
   if (DENSE) {
-    n_ent = min(N, (tile + 1) * kFwdBM) / kChunk;  // every chunk up to the tile's last row
+    n_ent = min(N, (tile + 1) * BM) / kChunk;  // every chunk up to the tile's last row
   } else {
-    ent_lo = p.q_tiles.ptr[h * T + tile];
-    n_ent = p.q_tiles.ptr[h * T + tile + 1] - ent_lo;
+    ent_lo = p.fwd_tiles.ptr[h * T + tile];
+    n_ent = p.fwd_tiles.ptr[h * T + tile + 1] - ent_lo;
   }
   const int total = n_ent * cpb;
 
@@ -76,34 +80,40 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(const AttnParams p) {
       kv0 = it * kChunk;
       keep = true;
     } else {
-      const int e = p.q_tiles.ent[ent_lo + it / cpb];
+      const int e = p.fwd_tiles.ent[ent_lo + it / cpb];
       kv0 = (e >> 8) * S + (it % cpb) * kChunk;
       keep = (e >> my_member) & 1;
     }
   };
 
-  f32x16 acc_o[D / 32];
+  f32x16 acc_o[QT][D / 32];
+  float m_run[QT], l_run[QT];
 #pragma unroll
-  for (int dt = 0; dt < D / 32; ++dt) acc_o[dt] = f32x16{};
-  float m_run = kNegInf;  // running max of the raw (unscaled) scores of my query
-  float l_run = 0.f;      // running sum over my half's key rows
+  for (int qt = 0; qt < QT; ++qt) {
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt) acc_o[qt][dt] = f32x16{};
+    m_run[qt] = kNegInf;  // running max of the raw (unscaled) scores of my query
+    l_run[qt] = 0.f;      // running sum over my half's key rows
+  }
   const float c = p.scale_log2e;
 
-  u32x4 kreg[RowTile<D>::kPerThread];
-  u32x4 vreg[4];
+  const typename DmaTile<D>::Plan plan = DmaTile<D>::plan(p.kv_st, wave, lane);
+  const int trb = DmaTile<D>::tr_base(lane);
   if (total > 0) {
     int kv0;
     bool keep;
     chunk_of(0, kv0, keep);
-    RowTile<D>::load(kreg, kb + (int64_t)kv0 * p.kv_st, p.kv_st, tid);
-    TransposedTile<D>::load(vreg, vb + (int64_t)kv0 * p.kv_st, p.kv_st, tid);
-    RowTile<D>::store(kreg, sm.k[0], tid);
-    TransposedTile<D>::store(vreg, sm.vt[0], tid);
+    DmaTile<D>::issue(plan, kb + (int64_t)kv0 * p.kv_st, sk[0], wave);
+    DmaTile<D>::issue(plan, vb + (int64_t)kv0 * p.kv_st, sv[0], wave);
   }
+  wait_all_loads();
   __syncthreads();
 
   for (int it = 0; it < total; ++it) {
-    const int buf = it & 1;
+    const uint16_t* ks = sk[it & 1];
+    const uint16_t* vs = sv[it & 1];
+    const uint16_t* kn = sk[(it & 1) ^ 1];
+    const uint16_t* vn = sv[(it & 1) ^ 1];
     int kv0;
     bool keep;
     chunk_of(it, kv0, keep);
@@ -111,114 +121,127 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(const AttnParams p) {
       int kv1;
       bool keep1;
       chunk_of(it + 1, kv1, keep1);
-      RowTile<D>::load(kreg, kb + (int64_t)kv1 * p.kv_st, p.kv_st, tid);
-      TransposedTile<D>::load(vreg, vb + (int64_t)kv1 * p.kv_st, p.kv_st, tid);
+      DmaTile<D>::issue(plan, kb + (int64_t)kv1 * p.kv_st, kn, wave);
+      DmaTile<D>::issue(plan, vb + (int64_t)kv1 * p.kv_st, vn, wave);
     }
 
-    // keys of this chunk all lie after every one of my 32 queries -> nothing to do
-    if (wave_active && keep && kv0 <= qw0 + 31) {
-      const uint16_t* ks = sm.k[buf];
-      const uint16_t* vs = sm.vt[buf];
-      f32x16 s[2] = {f32x16{}, f32x16{}};
+    // keys of this chunk all lie after every one of my queries -> nothing to do
+    if (wave_active && keep && kv0 <= qw0 + MW - 1) {
+      f32x16 s[QT][2];
 #pragma unroll
-      for (int kk = 0; kk < D / 16; ++kk) {
+      for (int qt = 0; qt < QT; ++qt) s[qt][0] = s[qt][1] = f32x16{};
+      // all K fragments of the chunk are requested before the first MFMA needs one
+      bf16x8 kfr[2][D / 16];
+#pragma unroll
+      for (int kk = 0; kk < D / 16; ++kk)
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt) kfr[kt][kk] = DmaTile<D>::row_frag(ks, kt, kk, l32, half);
+#pragma unroll
+      for (int kk = 0; kk < D / 16; ++kk)
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
-          s[kt] = mfma32(RowTile<D>::frag(ks, kt, kk, l32, half), qf[kk], s[kt]);
-      }
-      if (kv0 + kChunk - 1 > qw0) {  // diagonal chunk: key position must not exceed query position
-        const int qpos = qw0 + l32;
+#pragma unroll
+          for (int qt = 0; qt < QT; ++qt) s[qt][kt] = mfma32(kfr[kt][kk], qf[qt][kk], s[qt][kt]);
+      bf16x8 pb[QT][2][2];
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt) {
+        const int q0 = qw0 + 32 * qt;
+        if (kv0 + kChunk - 1 > q0) {  // diagonal: key position must not exceed query position
+          const int qpos = q0 + l32;
+#pragma unroll
+          for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int key = kv0 + 32 * kt + 8 * (r >> 2) + 4 * half + (r & 3);
+              if (key > qpos) s[qt][kt][r] = kNegInf;
+            }
+        }
+        float mx = s[qt][0][0];
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[qt][kt][r]);
+        mx = fmaxf(mx, other_half(mx));
+        // a sub-tile wholly above the diagonal has mx = -inf; keep the running max unchanged then
+        const float m_new = fmaxf(m_run[qt], mx);
+        const float m_use = (m_new == kNegInf) ? 0.f : m_new;
+        const float alpha = fast_exp2((m_run[qt] - m_use) * c);
+        const float mc = m_use * c;
+        float psum = 0.f;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const int key = kv0 + 32 * kt + 8 * (r >> 2) + 4 * half + (r & 3);
-            if (key > qpos) s[kt][r] = kNegInf;
+            s[qt][kt][r] = fast_exp2(__builtin_fmaf(s[qt][kt][r], c, -mc));
+            psum += s[qt][kt][r];
           }
-      }
-      float mx = s[0][0];
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
-      mx = fmaxf(mx, other_half(mx));
-      const float m_new = fmaxf(m_run, mx);
-      const float alpha = fast_exp2((m_run - m_new) * c);
-      const float mc = m_new * c;
-      float psum = 0.f;
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          s[kt][r] = fast_exp2(__builtin_fmaf(s[kt][r], c, -mc));
-          psum += s[kt][r];
-        }
-      l_run = l_run * alpha + psum;
-      if (__any(m_new != m_run)) {
-#pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc_o[dt][r] *= alpha;
-      }
-      m_run = m_new;
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          const bf16x8 pb = pack8(s[kt][8 * u + 0], s[kt][8 * u + 1], s[kt][8 * u + 2], s[kt][8 * u + 3],
-                                  s[kt][8 * u + 4], s[kt][8 * u + 5], s[kt][8 * u + 6], s[kt][8 * u + 7]);
+        l_run[qt] = l_run[qt] * alpha + psum;
+        if (__any(m_new != m_run[qt])) {
 #pragma unroll
           for (int dt = 0; dt < D / 32; ++dt)
-            acc_o[dt] = mfma32(TransposedTile<D>::frag(vs, dt, 2 * kt + u, l32, half), pb, acc_o[dt]);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc_o[qt][dt][r] *= alpha;
         }
+        m_run[qt] = m_new;
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+          for (int u = 0; u < 2; ++u)
+            pb[qt][kt][u] = pack8(s[qt][kt][8 * u + 0], s[qt][kt][8 * u + 1], s[qt][kt][8 * u + 2],
+                                  s[qt][kt][8 * u + 3], s[qt][kt][8 * u + 4], s[qt][kt][8 * u + 5],
+                                  s[qt][kt][8 * u + 6], s[qt][kt][8 * u + 7]);
+      }
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+          for (int dt = 0; dt < D / 32; ++dt) {
+            const bf16x8 a = DmaTile<D>::tr_frag(vs, dt, 2 * kt + u, trb);
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt) acc_o[qt][dt] = mfma32(a, pb[qt][kt][u], acc_o[qt][dt]);
+          }
     }
 
-    if (it + 1 < total) {
-      RowTile<D>::store(kreg, sm.k[buf ^ 1], tid);
-      TransposedTile<D>::store(vreg, sm.vt[buf ^ 1], tid);
-    }
+    wait_all_loads();
     __syncthreads();
   }
 
   if (!wave_active) return;
-  const float l_tot = l_run + other_half(l_run);
-  const float inv = 1.0f / l_tot;
-  const int qrow = qw0 + l32;
-  uint16_t* orow = p.o + b * p.q_sb + h * p.q_sh + (int64_t)qrow * p.q_st;
 #pragma unroll
-  for (int dt = 0; dt < D / 32; ++dt)
+  for (int qt = 0; qt < QT; ++qt) {
+    const float l_tot = l_run[qt] + other_half(l_run[qt]);
+    const float inv = 1.0f / l_tot;
+    const int qrow = qw0 + 32 * qt + l32;
+    uint16_t* orow = p.o + b * p.q_sb + h * p.q_sh + (int64_t)qrow * p.q_st;
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      bf16x4 w;
+    for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) w[e] = (__bf16)(acc_o[dt][4 * g + e] * inv);
-      *reinterpret_cast<bf16x4*>(orow + 32 * dt + 8 * g + 4 * half) = w;
-    }
-  if (half == 0)
-    p.lse[((int64_t)b * p.heads + h) * N + qrow] = m_run * p.scale + __logf(l_tot);
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = (__bf16)(acc_o[qt][dt][4 * g + e] * inv);
+        *reinterpret_cast<bf16x4*>(orow + 32 * dt + 8 * g + 4 * half) = w;
+      }
+    if (half == 0) p.lse[((int64_t)b * p.heads + h) * N + qrow] = m_run[qt] * p.scale + __logf(l_tot);
+  }
 }
 
-template <int D, bool DENSE>
+template <int D, bool DENSE, int QT>
 hipError_t launch_one(const AttnParams& p, hipStream_t stream) {
-  const int T = p.q_tiles.tiles_per_head;
+  const int T = p.fwd_tiles.tiles_per_head;
   const int grid = grid_for(p.batch * p.heads, T);
-  const size_t smem = sizeof(FwdSmem<D>);
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_kernel<D, DENSE>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
-  hipLaunchKernelGGL((fwd_kernel<D, DENSE>), dim3(grid), dim3(kThreads), smem, stream, p);
+  hipLaunchKernelGGL((fwd_kernel<D, DENSE, QT>), dim3(grid), dim3(kThreads), 0, stream, p);
   return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_fwd(const AttnParams& p, bool dense, hipStream_t stream) {
-  if (p.head_dim == 128) return dense ? launch_one<128, true>(p, stream) : launch_one<128, false>(p, stream);
-  return dense ? launch_one<64, true>(p, stream) : launch_one<64, false>(p, stream);
+  constexpr int QT = kFwdBM / 128;
+  if (p.head_dim == 128)
+    return dense ? launch_one<128, true, QT>(p, stream) : launch_one<128, false, QT>(p, stream);
+  return dense ? launch_one<64, true, QT>(p, stream) : launch_one<64, false, QT>(p, stream);
 }
 
 }  // namespace s2

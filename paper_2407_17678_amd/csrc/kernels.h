@@ -56,7 +56,6 @@ struct DecodeParams {
 
 // Each returns the hipError_t of the launch (hipGetLastError after the launch).
 hipError_t launch_fwd(const AttnParams& p, bool dense, hipStream_t stream);
-hipError_t launch_fwd2(const AttnParams& p, bool dense, hipStream_t stream);
 // `stages` selects which of the three backward launches run: 1 = delta, 2 = dK/dV, 4 = dQ.
 constexpr int kBwdDelta = 1, kBwdDkDv = 2, kBwdDq = 4, kBwdAll = 7;
 hipError_t launch_bwd(const AttnParams& p, bool dense, int stages, hipStream_t stream);
