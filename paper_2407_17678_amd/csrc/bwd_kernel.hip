@@ -98,14 +98,26 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
     n_ent = p.q_tiles.ptr[h * T + tile + 1] - ent_lo;
   }
   const int total = n_ent * cpb;
+  EntryList list;
+  if (!DENSE) list.init(p.q_tiles.ent + ent_lo, n_ent, lane);
+  // chunk `it` of the tile's list: its first row, and whether my mask row / column keeps it
   auto chunk_of = [&](int it, int& kv0, bool& keep) {
     if (DENSE) {
       kv0 = it * kChunk;
       keep = true;
     } else {
-      const int e = p.q_tiles.ent[ent_lo + it / cpb];
+      const int e = list.get(it / cpb, lane);
       kv0 = (e >> 8) * S + (it % cpb) * kChunk;
       keep = (e >> my_member) & 1;
+    }
+  };
+  // first row of chunk it+1, right after chunk_of(it)
+  auto next_chunk_of = [&](int it, int& kv0_n) {
+    if (DENSE) {
+      kv0_n = (it + 1) * kChunk;
+    } else {
+      const int e = (it + 1) / cpb == it / cpb ? list.get(it / cpb, lane) : list.peek_next(it / cpb);
+      kv0_n = (e >> 8) * S + ((it + 1) % cpb) * kChunk;
     }
   };
 
@@ -153,8 +165,7 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
     chunk_of(it, kv0, keep);
     if (it + 1 < total) {
       int kv1;
-      bool keep1;
-      chunk_of(it + 1, kv1, keep1);
+      next_chunk_of(it, kv1);
       DmaTile<D>::issue(plan, kb + (int64_t)kv1 * p.kv_st, sm.k[buf ^ 1], wave);
       DmaTile<D>::issue(plan, vb + (int64_t)kv1 * p.kv_st, sm.v[buf ^ 1], wave);
     }
@@ -265,14 +276,26 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
     n_ent = p.kv_tiles.ptr[h * T + tile + 1] - ent_lo;
   }
   const int total = n_ent * cpb;
+  EntryList list;
+  if (!DENSE) list.init(p.kv_tiles.ent + ent_lo, n_ent, lane);
+  // chunk `it` of the tile's list: its first row, and whether my mask row / column keeps it
   auto chunk_of = [&](int it, int& q0, bool& keep) {
     if (DENSE) {
       q0 = tile * kBwdBN + it * kChunk;
       keep = true;
     } else {
-      const int e = p.kv_tiles.ent[ent_lo + it / cpb];
+      const int e = list.get(it / cpb, lane);
       q0 = (e >> 8) * S + (it % cpb) * kChunk;
       keep = (e >> my_member) & 1;
+    }
+  };
+  // first row of chunk it+1, right after chunk_of(it)
+  auto next_chunk_of = [&](int it, int& q0_n) {
+    if (DENSE) {
+      q0_n = tile * kBwdBN + (it + 1) * kChunk;
+    } else {
+      const int e = (it + 1) / cpb == it / cpb ? list.get(it / cpb, lane) : list.peek_next(it / cpb);
+      q0_n = (e >> 8) * S + ((it + 1) % cpb) * kChunk;
     }
   };
 
@@ -323,8 +346,7 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
     chunk_of(it, q0, keep);
     if (it + 1 < total) {
       int q1;
-      bool keep1;
-      chunk_of(it + 1, q1, keep1);
+      next_chunk_of(it, q1);
       issue_chunk(q1, buf ^ 1);
     }
 

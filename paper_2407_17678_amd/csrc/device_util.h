@@ -57,8 +57,8 @@ __device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3, 
 // direct load fills.
 //
 // Direct loads write LDS at (wave-uniform base) + 16 * lane, so LDS position decides which global
-// address a lane fetches: position p holds row p / stride, 16-byte piece (p % stride) / 16; the
-// pad pieces at the end of each row fetch piece 0 of the same row (in bounds, never read).
+// address a lane fetches: position p holds row p / stride, 16-byte piece (p % stride) / 16; lanes
+// that fall on the pad pieces at the end of a row are masked off (nothing reads the padding).
 //
 // ds_read_b64_tr_b16, within each group of 16 lanes: lane 4e+q supplies the address of 4
 // consecutive bf16 (row e of a 4 x 16 block, piece q); lane i receives element i of rows 0..3.
@@ -95,7 +95,8 @@ struct DmaTile {
   static_assert(kBytes % 1024 == 0, "tile must be a whole number of wavefront loads");
 
   struct Plan {
-    int32_t goff[kPerWave];  // element offset from the chunk's first row, per load of this lane
+    int32_t goff[kPerWave];  // element offset from the chunk's first row, per load of this lane;
+                             // negative: this lane sits on row padding and fetches nothing
   };
 
   __device__ static __forceinline__ Plan plan(int64_t row_stride, int wave, int lane) {
@@ -104,9 +105,8 @@ struct DmaTile {
     for (int n = 0; n < kPerWave; ++n) {
       const int pos = (4 * n + wave) * 1024 + lane * 16;
       const int row = pos / (kStride * 2);
-      int piece = (pos - row * kStride * 2) / 16;
-      if (piece >= D / 8) piece = 0;
-      pl.goff[n] = (int32_t)(min(row, 63) * row_stride) + 8 * piece;
+      const int piece = (pos - row * kStride * 2) / 16;
+      pl.goff[n] = (piece < D / 8 && row < 64) ? (int32_t)(row * row_stride) + 8 * piece : -1;
     }
     return pl;
   }
@@ -118,7 +118,7 @@ struct DmaTile {
 #pragma unroll
     for (int n = 0; n < kPerWave; ++n) {
       const int instr = 4 * n + wave;
-      if (instr < kInstr) dma16(gbase + pl.goff[n], base + instr * 1024);
+      if (instr < kInstr && pl.goff[n] >= 0) dma16(gbase + pl.goff[n], base + instr * 1024);
     }
   }
 
@@ -146,6 +146,38 @@ struct DmaTile {
 
 // Everything outstanding (direct loads included) has landed.
 __device__ __forceinline__ void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory"); }
+
+// A tile's entry list, held in registers: lane i of the wavefront keeps entry 64*b + i of the
+// current batch of 64 entries, and the next batch is fetched one batch ahead, so the main loops
+// read their block index with v_readlane instead of waiting on global memory every iteration.
+struct EntryList {
+  const int32_t* ent;
+  int n;         // entries in the list
+  int batch;     // which batch of 64 `cur` holds
+  int cur, nxt;  // my entry of the current / next batch
+  __device__ __forceinline__ void init(const int32_t* list, int count, int lane) {
+    ent = list;
+    n = count;
+    batch = 0;
+    cur = lane < n ? ent[lane] : 0;
+    nxt = 64 + lane < n ? ent[64 + lane] : 0;
+  }
+  // entry e (wave-uniform); e never decreases between calls
+  __device__ __forceinline__ int get(int e, int lane) {
+    if ((e >> 6) != batch) {  // crossed into the next batch
+      batch = e >> 6;
+      cur = nxt;
+      const int i = 64 * (batch + 1) + lane;
+      nxt = i < n ? ent[i] : 0;
+    }
+    return __builtin_amdgcn_readlane(cur, e & 63);
+  }
+  // entry e+1, given that get(e) was the last call; does not advance
+  __device__ __forceinline__ int peek_next(int e) const {
+    return ((e + 1) >> 6) != batch ? __builtin_amdgcn_readlane(nxt, 0)
+                                   : __builtin_amdgcn_readlane(cur, (e + 1) & 63);
+  }
+};
 
 // Workgroup index -> (batch*head, rank inside the head) such that all tiles of one (batch, head)
 // run on one XCD.  Workgroups are handed to the 8 XCDs round-robin by linear index, and each XCD

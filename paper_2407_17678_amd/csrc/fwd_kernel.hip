@@ -75,14 +75,26 @@ __global__ __launch_bounds__(kThreads, (QT == 1 ? 2 : 1)) void fwd_kernel(const 
   const int total = n_ent * cpb;
 
   // chunk `it` of the tile's list: first key row, and whether my mask row keeps it
+  EntryList list;
+  if (!DENSE) list.init(p.fwd_tiles.ent + ent_lo, n_ent, lane);
+  // chunk `it` of the tile's list: its first row, and whether my mask row / column keeps it
   auto chunk_of = [&](int it, int& kv0, bool& keep) {
     if (DENSE) {
       kv0 = it * kChunk;
       keep = true;
     } else {
-      const int e = p.fwd_tiles.ent[ent_lo + it / cpb];
+      const int e = list.get(it / cpb, lane);
       kv0 = (e >> 8) * S + (it % cpb) * kChunk;
       keep = (e >> my_member) & 1;
+    }
+  };
+  // first row of chunk it+1, right after chunk_of(it)
+  auto next_chunk_of = [&](int it, int& kv0_n) {
+    if (DENSE) {
+      kv0_n = (it + 1) * kChunk;
+    } else {
+      const int e = (it + 1) / cpb == it / cpb ? list.get(it / cpb, lane) : list.peek_next(it / cpb);
+      kv0_n = (e >> 8) * S + ((it + 1) % cpb) * kChunk;
     }
   };
 
@@ -119,8 +131,7 @@ __global__ __launch_bounds__(kThreads, (QT == 1 ? 2 : 1)) void fwd_kernel(const 
     chunk_of(it, kv0, keep);
     if (it + 1 < total) {
       int kv1;
-      bool keep1;
-      chunk_of(it + 1, kv1, keep1);
+      next_chunk_of(it, kv1);
       DmaTile<D>::issue(plan, kb + (int64_t)kv1 * p.kv_st, kn, wave);
       DmaTile<D>::issue(plan, vb + (int64_t)kv1 * p.kv_st, vn, wave);
     }
