@@ -70,7 +70,7 @@ int check_tensors(const s2_tensors* t, bool need_bwd, float scale) {
   for (int64_t s : strides)
     if (s < 0 || (s & 7) != 0) return S2_ERR_ALIGN;
   if (t->q_stride_t < t->head_dim || t->kv_stride_t < t->head_dim) return S2_ERR_ALIGN;
-  // the kernels address the 64 rows of a chunk with 32-bit element offsets
+  // the kernels address the 64 rows of a chunk with unsigned 32-bit byte offsets
   if (t->q_stride_t > (1 << 24) || t->kv_stride_t > (1 << 24)) return S2_ERR_SHAPE;
   const void* ptrs[9] = {t->q, t->k, t->v, t->o, t->lse, t->d_o, t->dq, t->dk, t->dv};
   for (int i = 0; i < (need_bwd ? 9 : 5); ++i)

@@ -305,8 +305,8 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
     DmaTile<D>::issue(plan, qb + (int64_t)q0 * p.q_st, sm.q[buf], wave);
     DmaTile<D>::issue(plan, gb + (int64_t)q0 * p.q_st, sm.g[buf], wave);
     // 64 floats each: one 4-byte direct load per lane
-    if (wave == 0) dma4(lse_b + q0 + lane, lds_addr(sm.lse[buf]));
-    if (wave == 1) dma4(delta_b + q0 + lane, lds_addr(sm.delta[buf]));
+    if (wave == 0) dma4(lse_b + q0, 4 * lane, lds_addr(sm.lse[buf]));
+    if (wave == 1) dma4(delta_b + q0, 4 * lane, lds_addr(sm.delta[buf]));
   };
   if (total > 0) {
     int q0;

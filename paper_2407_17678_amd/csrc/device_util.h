@@ -78,11 +78,15 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
 // not make unrelated LDS reads wait for a prefetch in flight; the kernels wait for them explicitly
 // (wait_all_loads) before the barrier that publishes a stage.  Untracked loads only make the
 // compiler's own vmcnt waits more conservative, never less (the counter retires in order).
-__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
+// The global address is a wave-uniform base (scalar registers) plus a per-lane unsigned 32-bit
+// byte offset, so a lane spends one register per load and no 64-bit address arithmetic.
+__device__ __forceinline__ void dma16(const void* gbase, uint32_t byte_off, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(gbase), "s"(lds_base)
+               : "memory");
 }
-__device__ __forceinline__ void dma4(const void* gptr, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
+__device__ __forceinline__ void dma4(const void* gbase, uint32_t byte_off, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dword %0, %1" ::"v"(byte_off), "s"(gbase), "s"(lds_base)
+               : "memory");
 }
 
 template <int D>
@@ -94,9 +98,10 @@ struct DmaTile {
   static constexpr int kPerWave = (kInstr + 3) / 4;
   static_assert(kBytes % 1024 == 0, "tile must be a whole number of wavefront loads");
 
+  static constexpr uint32_t kSkip = 0xffffffffu;
   struct Plan {
-    int32_t goff[kPerWave];  // element offset from the chunk's first row, per load of this lane;
-                             // negative: this lane sits on row padding and fetches nothing
+    uint32_t goff[kPerWave];  // byte offset from the chunk's first row, per load of this lane;
+                              // kSkip: this lane sits on row padding and fetches nothing
   };
 
   __device__ static __forceinline__ Plan plan(int64_t row_stride, int wave, int lane) {
@@ -106,7 +111,7 @@ struct DmaTile {
       const int pos = (4 * n + wave) * 1024 + lane * 16;
       const int row = pos / (kStride * 2);
       const int piece = (pos - row * kStride * 2) / 16;
-      pl.goff[n] = (piece < D / 8 && row < 64) ? (int32_t)(row * row_stride) + 8 * piece : -1;
+      pl.goff[n] = (piece < D / 8 && row < 64) ? (uint32_t)(row * row_stride * 2) + 16 * piece : kSkip;
     }
     return pl;
   }
@@ -118,8 +123,15 @@ struct DmaTile {
 #pragma unroll
     for (int n = 0; n < kPerWave; ++n) {
       const int instr = 4 * n + wave;
-      if (instr < kInstr && pl.goff[n] >= 0) dma16(gbase + pl.goff[n], base + instr * 1024);
+      if (instr < kInstr && pl.goff[n] != kSkip) dma16(gbase, pl.goff[n], base + instr * 1024);
     }
+  }
+
+  // One of the kPerWave loads of `issue`, so that a kernel can spread them between MFMAs.
+  __device__ static __forceinline__ void issue_one(const Plan& pl, int n, const uint16_t* gbase,
+                                                   const uint16_t* tile, int wave) {
+    const int instr = 4 * n + wave;
+    if (instr < kInstr && pl.goff[n] != kSkip) dma16(gbase, pl.goff[n], lds_addr(tile) + instr * 1024);
   }
 
   // row fragment: row = 32*rt + lane%32, features 16*kk + 8*half .. +7
@@ -144,8 +156,14 @@ struct DmaTile {
   }
 };
 
-// Everything outstanding (direct loads included) has landed.
-__device__ __forceinline__ void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory"); }
+// Everything outstanding (direct loads included) has landed.  This is the builtin, not inline
+// assembly, so that the compiler also learns that its own earlier loads (fragments fetched before
+// a loop, say) are complete: otherwise it keeps re-waiting for them inside the loop with small
+// vmcnt values, and such a wait drains the untracked direct loads that were issued after them.
+__device__ __forceinline__ void wait_all_loads() {
+  __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0) expcnt(0) lgkmcnt(0)
+  asm volatile("" ::: "memory");
+}
 
 // A tile's entry list, held in registers: lane i of the wavefront keeps entry 64*b + i of the
 // current batch of 64 entries, and the next batch is fetched one batch ahead, so the main loops

@@ -129,15 +129,26 @@ __global__ __launch_bounds__(kThreads, (QT == 1 ? 2 : 1)) void fwd_kernel(const 
     int kv0;
     bool keep;
     chunk_of(it, kv0, keep);
-    if (it + 1 < total) {
+    // The next chunk's direct loads are spread between the MFMAs of the first contraction (the
+    // address unit takes a load every ~16 cycles, an MFMA 32), or issued at once by a wavefront
+    // that has nothing to compute for this chunk.
+    const bool prefetch = it + 1 < total;
+    const bool compute = wave_active && keep && kv0 <= qw0 + MW - 1;
+    const uint16_t* kg = kb;
+    const uint16_t* vg = vb;
+    if (prefetch) {
       int kv1;
       next_chunk_of(it, kv1);
-      DmaTile<D>::issue(plan, kb + (int64_t)kv1 * p.kv_st, kn, wave);
-      DmaTile<D>::issue(plan, vb + (int64_t)kv1 * p.kv_st, vn, wave);
+      kg = kb + (int64_t)kv1 * p.kv_st;
+      vg = vb + (int64_t)kv1 * p.kv_st;
+      if (!compute) {
+        DmaTile<D>::issue(plan, kg, kn, wave);
+        DmaTile<D>::issue(plan, vg, vn, wave);
+      }
     }
 
     // keys of this chunk all lie after every one of my queries -> nothing to do
-    if (wave_active && keep && kv0 <= qw0 + MW - 1) {
+    if (compute) {
       f32x16 s[QT][2];
 #pragma unroll
       for (int qt = 0; qt < QT; ++qt) s[qt][0] = s[qt][1] = f32x16{};
@@ -150,9 +161,14 @@ __global__ __launch_bounds__(kThreads, (QT == 1 ? 2 : 1)) void fwd_kernel(const 
 #pragma unroll
       for (int kk = 0; kk < D / 16; ++kk)
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
+        for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
           for (int qt = 0; qt < QT; ++qt) s[qt][kt] = mfma32(kfr[kt][kk], qf[qt][kk], s[qt][kt]);
+          constexpr int PW = DmaTile<D>::kPerWave;
+          const int n = 2 * kk + kt;
+          if (prefetch && n < PW) DmaTile<D>::issue_one(plan, n, kg, kn, wave);
+          if (prefetch && n >= PW && n < 2 * PW) DmaTile<D>::issue_one(plan, n - PW, vg, vn, wave);
+        }
       bf16x8 pb[QT][2][2];
 #pragma unroll
       for (int qt = 0; qt < QT; ++qt) {
