@@ -185,14 +185,16 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
         for (int kk = 0; kk < D / 16; ++kk) dp = mfma32(DmaTile<D>::row_frag(vs, kt, kk, l32, half), gf[kk], dp);
         const bool diag = kbase + 31 > qw0;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float pr = fast_exp2(__builtin_fmaf(s[r], c, -lse_l));
-          if (diag) {
+        for (int r = 0; r < 16; ++r) s[r] = fast_exp2(__builtin_fmaf(s[r], c, -lse_l));
+        if (diag) {  // only the half-chunks on the diagonal pay for the causal mask
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
             const int key = kbase + 8 * (r >> 2) + 4 * half + (r & 3);
-            if (key > qpos) pr = 0.f;
+            if (key > qpos) s[r] = 0.f;
           }
-          s[r] = pr * (dp[r] - delta_l);
         }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] *= dp[r] - delta_l;
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
           const bf16x8 dsb = pack8(s[8 * u + 0], s[8 * u + 1], s[8 * u + 2], s[8 * u + 3], s[8 * u + 4],
