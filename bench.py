@@ -49,6 +49,21 @@ def time_events(fn, steps, warmup):
     return e0.elapsed_time(e1) / steps
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary
+    (profiles/traffic_<workload>.txt, lines `<kernel> <bytes>`), or None."""
+    path = os.path.join(ROOT, "profiles", "traffic_%s.txt" % workload)
+    try:
+        with open(path) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) >= 2 and parts[0] == kernel:
+                    return float(parts[1])
+    except OSError:
+        pass
+    return None
+
+
 def bench_train(w, steps, warmup, with_dense=True, with_bwd=True, dense_steps=3):
     """Times fwd(+bwd) of workload `w`; returns a dict of timings and derived rates."""
     import torch
@@ -139,7 +154,7 @@ def bench_train(w, steps, warmup, with_dense=True, with_bwd=True, dense_steps=3)
     dom = max(kernels, key=lambda n: kernels[n][0])
     ach = kernels[dom][1] * D * pairs / (kernels[dom][0] * 1e-3) / 1e12
     res["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
-                       "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
+                       "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": measured_traffic(w.name, dom),
                        "avg_launch_ms": kernels[dom][0],
                        "algorithmic_flops_per_launch": kernels[dom][1] * D * pairs}
     tensors = dict(q=q, k=k, v=v, g=g, o=o, lse=lse, dq=dq, dk=dk, dv=dv, bits=(qb, kb, vb, gb))
@@ -247,6 +262,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--extra", action="store_true", help="also time the other workloads (reported under 'extra')")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="first run a 1 GiB device-to-device copy, so that a rocprofv3 --pmc run has a kernel "
+                         "of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; --gpus %d is not supported (heads and batch "
@@ -262,6 +280,13 @@ def main():
     B.lib()
     torch.cuda.set_device(0)
     w = synth.WORKLOADS[args.workload]
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     if w.kind == "decode":
         d = bench_decode(w, args.steps, args.warmup)
@@ -270,7 +295,8 @@ def main():
                "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
                "data": "synthetic", "config": d,
                "roofline": {"kernel": "decode_split_kernel", "bound": "hbm", "achieved": d["hbm_gbs"],
-                            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": d["frac_hbm_peak"], "traffic": None},
+                            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": d["frac_hbm_peak"],
+                            "traffic": measured_traffic(w.name, "decode_split_kernel")},
                "cpu_baseline": None}
         print(json.dumps(out))
         return
