@@ -283,21 +283,21 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
   // chunk `it` of the tile's list: its first row, and whether my mask row / column keeps it
   auto chunk_of = [&](int it, int& q0, bool& keep) {
     if (DENSE) {
-      q0 = tile * kBwdBN + it * kChunk;
+      q0 = N - kChunk - it * kChunk;  // from the last query chunk down, like the sparse lists
       keep = true;
     } else {
       const int e = list.get(it / cpb, lane);
-      q0 = (e >> 8) * S + (it % cpb) * kChunk;
+      q0 = (e >> 8) * S + (cpb - 1 - it % cpb) * kChunk;
       keep = (e >> my_member) & 1;
     }
   };
   // first row of chunk it+1, right after chunk_of(it)
   auto next_chunk_of = [&](int it, int& q0_n) {
     if (DENSE) {
-      q0_n = tile * kBwdBN + (it + 1) * kChunk;
+      q0_n = N - kChunk - (it + 1) * kChunk;
     } else {
       const int e = (it + 1) / cpb == it / cpb ? list.get(it / cpb, lane) : list.peek_next(it / cpb);
-      q0_n = (e >> 8) * S + ((it + 1) % cpb) * kChunk;
+      q0_n = (e >> 8) * S + (cpb - 1 - (it + 1) % cpb) * kChunk;
     }
   };
 

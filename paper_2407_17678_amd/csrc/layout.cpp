@@ -165,6 +165,10 @@ void build_tiles(const s2_layout& L, int group, bool transpose, TileList& out) {
           if (cur[r] < end[r] && idx[cur[r]] == best) { bits |= 1 << r; ++cur[r]; }
         out.ent.push_back((int32_t)((best << 8) | bits));
       }
+      // Column tiles are walked from the last query block down.  Every stripe tile of a head ends
+      // at the last row, so tiles started together then read the same Q / dO blocks at the same
+      // time and share them in L2 instead of each streaming them from HBM.
+      if (transpose) std::reverse(out.ent.begin() + start, out.ent.end());
       const int len = (int)(out.ent.size() - start);
       out.max_len = std::max(out.max_len, len);
       out.ptr[(size_t)h * T + t + 1] = (int32_t)out.ent.size();

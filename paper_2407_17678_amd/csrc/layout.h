@@ -18,7 +18,8 @@ struct TileList {
   int group = 0;                 // members per tile (1..8)
   int tiles_per_head = 0;        // ceil(B / group)
   std::vector<int32_t> ptr;      // [H*tiles_per_head + 1]
-  std::vector<int32_t> ent;      // packed entries, partner ascending inside a tile
+  std::vector<int32_t> ent;      // packed entries; partner ascending inside a row tile,
+                                 // descending inside a column tile
   std::vector<int32_t> order;    // [H*tiles_per_head]: per head, tile ids by descending length
   std::vector<int32_t> members;  // [H*tiles_per_head*group]: block index of each member, -1 = none
   int32_t* d_ptr = nullptr;      // device copies (owned by the layout)
