@@ -229,8 +229,10 @@ template <int D>
 struct DkvSmem {
   uint16_t q[2][DmaTile<D>::kElems];
   uint16_t g[2][DmaTile<D>::kElems];
-  float lse[2][kChunk];    // base-2 units
-  float delta[2][kChunk];
+  struct RowStats {
+    float delta[kChunk];
+    float lse[kChunk];     // base-2 units
+  } rs[2];                 // one 512-byte direct load fills both arrays of a stage
 };
 
 template <int D, bool DENSE>
@@ -303,12 +305,14 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
 
   const typename DmaTile<D>::Plan plan = DmaTile<D>::plan(p.q_st, wave, lane);
   const int trb = DmaTile<D>::tr_base(lane);
+  const uint32_t stats_off =
+      lane < 16 ? 16 * lane : (uint32_t)((const char*)lse_b - (const char*)delta_b) + 16 * (lane - 16);
   auto issue_chunk = [&](int q0, int buf) {
     DmaTile<D>::issue(plan, qb + (int64_t)q0 * p.q_st, sm.q[buf], wave);
     DmaTile<D>::issue(plan, gb + (int64_t)q0 * p.q_st, sm.g[buf], wave);
-    // 64 floats each: one 4-byte direct load per lane
-    if (wave == 0) dma4(lse_b + q0, 4 * lane, lds_addr(sm.lse[buf]));
-    if (wave == 1) dma4(delta_b + q0, 4 * lane, lds_addr(sm.delta[buf]));
+    // 64 floats of each array = 2 x 256 bytes: lanes 0..15 fetch delta, lanes 16..31 lse, in one
+    // direct load issued by the wavefront that has one load fewer than the others in the two tiles
+    if (wave == 3 && lane < 32) dma16(delta_b + q0, stats_off, lds_addr(&sm.rs[buf]));
   };
   if (total > 0) {
     int q0;
@@ -369,8 +373,8 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const int r0 = 32 * qt + 8 * g + 4 * half;
-          const f32x4 l4 = *reinterpret_cast<const f32x4*>(&sm.lse[buf][r0]);
-          const f32x4 d4 = *reinterpret_cast<const f32x4*>(&sm.delta[buf][r0]);
+          const f32x4 l4 = *reinterpret_cast<const f32x4*>(&sm.rs[buf].lse[r0]);
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(&sm.rs[buf].delta[r0]);
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int r = 4 * g + e;
