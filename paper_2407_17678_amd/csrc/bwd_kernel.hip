@@ -304,21 +304,23 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
   };
 
   const typename DmaTile<D>::Plan plan = DmaTile<D>::plan(p.q_st, wave, lane);
-  const int trb = DmaTile<D>::tr_base(lane);
-  const uint32_t stats_off =
-      lane < 16 ? 16 * lane : (uint32_t)((const char*)lse_b - (const char*)delta_b) + 16 * (lane - 16);
-  auto issue_chunk = [&](int q0, int buf) {
+  const uint32_t stats_gap = (uint32_t)((const char*)lse_b - (const char*)delta_b);
+  // `ln` is the lane number.  The loop passes a copy the optimiser cannot see through, so that
+  // what is derived from it is recomputed each step (a few integer operations) rather than kept in
+  // registers across the loop: this kernel has no registers to spare, and a spilled constant costs
+  // a wait for all outstanding loads when it is fetched back.
+  auto issue_chunk = [&](int q0, int buf, int ln) {
     DmaTile<D>::issue(plan, qb + (int64_t)q0 * p.q_st, sm.q[buf], wave);
     DmaTile<D>::issue(plan, gb + (int64_t)q0 * p.q_st, sm.g[buf], wave);
     // 64 floats of each array = 2 x 256 bytes: lanes 0..15 fetch delta, lanes 16..31 lse, in one
     // direct load issued by the wavefront that has one load fewer than the others in the two tiles
-    if (wave == 3 && lane < 32) dma16(delta_b + q0, stats_off, lds_addr(&sm.rs[buf]));
+    if (wave == 3 && ln < 32) dma16(delta_b + q0, 16 * ln + (ln < 16 ? 0u : stats_gap - 256u), lds_addr(&sm.rs[buf]));
   };
   if (total > 0) {
     int q0;
     bool keep;
     chunk_of(0, q0, keep);
-    issue_chunk(q0, 0);
+    issue_chunk(q0, 0, lane);
   }
 
   bf16x8 kf[D / 16], vf[D / 16];  // K and V fragments (B operands), lane = key
@@ -347,18 +349,22 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
 
   for (int it = 0; it < total; ++it) {
     const int buf = it & 1;
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
     int q0;
     bool keep;
     chunk_of(it, q0, keep);
     if (it + 1 < total) {
       int q1;
       next_chunk_of(it, q1);
-      issue_chunk(q1, buf ^ 1);
+      issue_chunk(q1, buf ^ 1, ln);
     }
 
     if (wave_active && keep && q0 + kChunk - 1 >= kvw0) {
       const uint16_t* qs = sm.q[buf];
       const uint16_t* gs = sm.g[buf];
+      const int l32 = ln & 31, half = ln >> 5;
+      const int trb = DmaTile<D>::tr_base(ln);
       const int key = kvw0 + l32;
 #pragma unroll
       for (int qt = 0; qt < 2; ++qt) {
