@@ -32,8 +32,28 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Value held by the lane 32 positions away (the other half of the wavefront).
-__device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32, 64); }
+// x of this lane combined with x of the lane 32 positions away (the other half of the wavefront).
+// v_permlane32_swap exchanges the upper half of one register with the lower half of another: fed
+// the same value twice it leaves one register holding the lower half's values in both halves and
+// the other the upper half's, so no trip through LDS (and no wait on the LDS counter) is needed.
+// Written as inline assembly: with this compiler the builtin's two results come back as one and
+// the same register.  The s_nop covers the wait states the instruction needs after a VALU write of
+// its operands (the compiler cannot see into the assembly to add them).
+__device__ __forceinline__ void swap_halves(float x, float& lo, float& hi) {
+  lo = x;
+  hi = x;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(lo), "+v"(hi));
+}
+__device__ __forceinline__ float max_halves(float x) {
+  float a, b;
+  swap_halves(x, a, b);
+  return fmaxf(a, b);
+}
+__device__ __forceinline__ float sum_halves(float x) {
+  float a, b;
+  swap_halves(x, a, b);
+  return a + b;
+}
 
 // Eight floats -> eight bf16 (round to nearest even, hardware conversion on gfx950).
 __device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3, float a4, float a5,

@@ -188,7 +188,7 @@ __global__ __launch_bounds__(kThreads, (QT == 1 ? 2 : 1)) void fwd_kernel(const 
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
           for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[qt][kt][r]);
-        mx = fmaxf(mx, other_half(mx));
+        mx = max_halves(mx);
         // a sub-tile wholly above the diagonal has mx = -inf; keep the running max unchanged then
         const float m_new = fmaxf(m_run[qt], mx);
         const float m_use = (m_new == kNegInf) ? 0.f : m_new;
@@ -237,7 +237,7 @@ __global__ __launch_bounds__(kThreads, (QT == 1 ? 2 : 1)) void fwd_kernel(const 
   if (!wave_active) return;
 #pragma unroll
   for (int qt = 0; qt < QT; ++qt) {
-    const float l_tot = l_run[qt] + other_half(l_run[qt]);
+    const float l_tot = sum_halves(l_run[qt]);
     const float inv = 1.0f / l_tot;
     const int qrow = qw0 + 32 * qt + l32;
     uint16_t* orow = p.o + b * p.q_sb + h * p.q_sh + (int64_t)qrow * p.q_st;
