@@ -78,7 +78,8 @@ __device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3, 
 //
 // Direct loads write LDS at (wave-uniform base) + 16 * lane, so LDS position decides which global
 // address a lane fetches: position p holds row p / stride, 16-byte piece (p % stride) / 16; lanes
-// that fall on the pad pieces at the end of a row are masked off (nothing reads the padding).
+// that fall on the pad pieces at the end of a row fetch something harmless (nothing reads the
+// padding).
 //
 // ds_read_b64_tr_b16, within each group of 16 lanes: lane 4e+q supplies the address of 4
 // consecutive bf16 (row e of a 4 x 16 block, piece q); lane i receives element i of rows 0..3.
@@ -109,49 +110,50 @@ __device__ __forceinline__ void dma4(const void* gbase, uint32_t byte_off, uint3
                : "memory");
 }
 
-template <int D>
+template <int D, int ROWS = 64>
 struct DmaTile {
   static constexpr int kStride = (D == 128) ? 152 : 104;  // elements
-  static constexpr int kElems = 64 * kStride;
-  static constexpr int kBytes = kElems * 2;
-  static constexpr int kInstr = kBytes / 1024;            // wavefront-wide loads per tile
+  static constexpr int kInstr = (ROWS * kStride * 2 + 1023) / 1024;  // wavefront-wide loads per tile
+  static constexpr int kBytes = kInstr * 1024;            // the last load may run past the last row
+  static constexpr int kElems = kBytes / 2;
   static constexpr int kPerWave = (kInstr + 3) / 4;
-  static_assert(kBytes % 1024 == 0, "tile must be a whole number of wavefront loads");
 
-  static constexpr uint32_t kSkip = 0xffffffffu;
   struct Plan {
-    uint32_t goff[kPerWave];  // byte offset from the chunk's first row, per load of this lane;
-                              // kSkip: this lane sits on row padding and fetches nothing
+    uint32_t goff[kPerWave];  // byte offset from the chunk's first row, per load of this lane
   };
 
+  // Every lane of every load gets a valid address, so that the loads need no branches around them
+  // (a branch would also split the basic block and keep the compiler from scheduling MFMAs and
+  // loads together): a lane that falls on row padding fetches a piece of its row again (it lands
+  // in the padding, which nothing reads), and a wavefront with one load fewer than the others
+  // repeats its last one.
   __device__ static __forceinline__ Plan plan(int64_t row_stride, int wave, int lane) {
     Plan pl;
 #pragma unroll
     for (int n = 0; n < kPerWave; ++n) {
-      const int pos = (4 * n + wave) * 1024 + lane * 16;
-      const int row = pos / (kStride * 2);
-      const int piece = (pos - row * kStride * 2) / 16;
-      pl.goff[n] = (piece < D / 8 && row < 64) ? (uint32_t)(row * row_stride * 2) + 16 * piece : kSkip;
+      const int instr = min(4 * n + wave, kInstr - 1);
+      const int pos = instr * 1024 + lane * 16;
+      int row = pos / (kStride * 2);
+      int piece = (pos - row * kStride * 2) / 16;
+      if (piece >= D / 8) piece -= D / 8;
+      if (row >= ROWS) row = ROWS - 1;  // past the tile: lands in the slack after the last row
+      pl.goff[n] = (uint32_t)(row * row_stride * 2) + 16 * piece;
     }
     return pl;
   }
 
-  // Starts the loads of one chunk; they are complete after s_waitcnt vmcnt(0).
-  __device__ static __forceinline__ void issue(const Plan& pl, const uint16_t* gbase, const uint16_t* tile,
-                                               int wave) {
-    const uint32_t base = lds_addr(tile);
-#pragma unroll
-    for (int n = 0; n < kPerWave; ++n) {
-      const int instr = 4 * n + wave;
-      if (instr < kInstr && pl.goff[n] != kSkip) dma16(gbase, pl.goff[n], base + instr * 1024);
-    }
-  }
-
-  // One of the kPerWave loads of `issue`, so that a kernel can spread them between MFMAs.
+  // One of the kPerWave loads of a chunk, so that a kernel can spread them between MFMAs.
+  // Complete after s_waitcnt vmcnt(0).
   __device__ static __forceinline__ void issue_one(const Plan& pl, int n, const uint16_t* gbase,
                                                    const uint16_t* tile, int wave) {
-    const int instr = 4 * n + wave;
-    if (instr < kInstr && pl.goff[n] != kSkip) dma16(gbase, pl.goff[n], lds_addr(tile) + instr * 1024);
+    const int instr = min(4 * n + wave, kInstr - 1);
+    dma16(gbase, pl.goff[n], lds_addr(tile) + instr * 1024);
+  }
+  // All loads of one chunk.
+  __device__ static __forceinline__ void issue(const Plan& pl, const uint16_t* gbase, const uint16_t* tile,
+                                               int wave) {
+#pragma unroll
+    for (int n = 0; n < kPerWave; ++n) issue_one(pl, n, gbase, tile, wave);
   }
 
   // row fragment: row = 32*rt + lane%32, features 16*kk + 8*half .. +7
@@ -209,6 +211,10 @@ struct EntryList {
       nxt = i < n ? ent[i] : 0;
     }
     return __builtin_amdgcn_readlane(cur, e & 63);
+  }
+  // entry j of the current or the next batch (64*batch <= j < 64*batch + 128); does not advance
+  __device__ __forceinline__ int peek(int j) const {
+    return (j >> 6) != batch ? __builtin_amdgcn_readlane(nxt, j & 63) : __builtin_amdgcn_readlane(cur, j & 63);
   }
   // entry e+1, given that get(e) was the last call; does not advance
   __device__ __forceinline__ int peek_next(int e) const {

@@ -25,12 +25,18 @@ namespace {
 constexpr float kNegInf = -__builtin_inff();
 
 
-template <int D, bool DENSE, int QT>
-__global__ __launch_bounds__(kThreads, (QT == 1 ? 2 : 1)) void fwd_kernel(const AttnParams p) {
-  __shared__ __attribute__((aligned(16))) uint16_t sk[2][DmaTile<D>::kElems];
-  __shared__ __attribute__((aligned(16))) uint16_t sv[2][DmaTile<D>::kElems];
-  constexpr int BM = 128 * QT;
-  constexpr int MW = 32 * QT;  // rows per wavefront
+// CH = keys per step (one LDS stage), 64 or 32.  With 32 a workgroup needs half the LDS and fewer
+// registers, so three workgroups fit a CU instead of two; measured, that is no faster (twice the
+// barriers for the same work), so 64 is what is instantiated.
+template <int D, bool DENSE, int CH>
+__global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const AttnParams p) {
+  typedef DmaTile<D, CH> Tile;
+  __shared__ __attribute__((aligned(16))) uint16_t sk[2][Tile::kElems];
+  __shared__ __attribute__((aligned(16))) uint16_t sv[2][Tile::kElems];
+  constexpr int BM = kFwdBM;
+  constexpr int MW = 32;       // rows per wavefront
+  constexpr int KT = CH / 32;  // 32-key score tiles per step
+  static_assert(BM == 4 * MW, "four wavefronts of 32 query rows");
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -41,7 +47,7 @@ __global__ __launch_bounds__(kThreads, (QT == 1 ? 2 : 1)) void fwd_kernel(const 
   const int b = bh / p.heads, h = bh - b * p.heads;
   const int tile = DENSE ? (T - 1 - rank) : p.fwd_tiles.order[h * T + rank];
   const int S = DENSE ? kChunk : p.block_size;
-  const int cpb = S / kChunk;  // 64-key chunks per mask block
+  const int cpb = S / CH;  // steps per mask block
 
   const int N = p.seqlen;
   const int qw0 = tile * BM + wave * MW;  // first query row of this wavefront
@@ -53,70 +59,63 @@ __global__ __launch_bounds__(kThreads, (QT == 1 ? 2 : 1)) void fwd_kernel(const 
   const uint16_t* vb = p.v + b * p.kv_sb + h * p.kv_sh;
 
   // Q^T fragments stay in registers for the whole tile.
-  bf16x8 qf[QT][D / 16];
+  bf16x8 qf[D / 16];
 #pragma unroll
-  for (int qt = 0; qt < QT; ++qt)
-#pragma unroll
-    for (int kk = 0; kk < D / 16; ++kk) {
-      if (wave_active)
-        qf[qt][kk] = *reinterpret_cast<const bf16x8*>(qb + (int64_t)(qw0 + 32 * qt + l32) * p.q_st + 16 * kk +
-                                                      8 * half);
-      else
-        qf[qt][kk] = bf16x8{};
-    }
+  for (int kk = 0; kk < D / 16; ++kk) {
+    if (wave_active)
+      qf[kk] = *reinterpret_cast<const bf16x8*>(qb + (int64_t)(qw0 + l32) * p.q_st + 16 * kk + 8 * half);
+    else
+      qf[kk] = bf16x8{};
+  }
 
   int ent_lo = 0, n_ent;
   if (DENSE) {
-    n_ent = min(N, (tile + 1) * BM) / kChunk;  // every chunk up to the tile's last row
+    n_ent = min(N, (tile + 1) * BM) / kChunk;  // every block up to the tile's last row
   } else {
     ent_lo = p.fwd_tiles.ptr[h * T + tile];
     n_ent = p.fwd_tiles.ptr[h * T + tile + 1] - ent_lo;
   }
   const int total = n_ent * cpb;
 
-  // chunk `it` of the tile's list: first key row, and whether my mask row keeps it
   EntryList list;
   if (!DENSE) list.init(p.fwd_tiles.ent + ent_lo, n_ent, lane);
-  // chunk `it` of the tile's list: its first row, and whether my mask row / column keeps it
+  // step `it` of the tile's list: its first key row, and whether my mask row keeps the block
   auto chunk_of = [&](int it, int& kv0, bool& keep) {
     if (DENSE) {
-      kv0 = it * kChunk;
+      kv0 = it * CH;
       keep = true;
     } else {
       const int e = list.get(it / cpb, lane);
-      kv0 = (e >> 8) * S + (it % cpb) * kChunk;
+      kv0 = (e >> 8) * S + (it % cpb) * CH;
       keep = (e >> my_member) & 1;
     }
   };
-  // first row of chunk it+1, right after chunk_of(it)
+  // first key row of step it+1, right after chunk_of(it)
   auto next_chunk_of = [&](int it, int& kv0_n) {
     if (DENSE) {
-      kv0_n = (it + 1) * kChunk;
+      kv0_n = (it + 1) * CH;
     } else {
       const int e = (it + 1) / cpb == it / cpb ? list.get(it / cpb, lane) : list.peek_next(it / cpb);
-      kv0_n = (e >> 8) * S + ((it + 1) % cpb) * kChunk;
+      kv0_n = (e >> 8) * S + ((it + 1) % cpb) * CH;
     }
   };
 
-  f32x16 acc_o[QT][D / 32];
-  float m_run[QT], l_run[QT];
+  f32x16 acc_o[D / 32];
 #pragma unroll
-  for (int qt = 0; qt < QT; ++qt) {
-#pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt) acc_o[qt][dt] = f32x16{};
-    m_run[qt] = kNegInf;  // running max of the raw (unscaled) scores of my query
-    l_run[qt] = 0.f;      // running sum over my half's key rows
-  }
+  for (int dt = 0; dt < D / 32; ++dt) acc_o[dt] = f32x16{};
+  float m_run = kNegInf;  // running max of the raw (unscaled) scores of my query
+  float l_run = 0.f;      // running sum over my half's key rows
   const float c = p.scale_log2e;
 
-  const typename DmaTile<D>::Plan plan = DmaTile<D>::plan(p.kv_st, wave, lane);
-  const int trb = DmaTile<D>::tr_base(lane);
+  const typename Tile::Plan plan = Tile::plan(p.kv_st, wave, lane);
+  const int trb = Tile::tr_base(lane);
+  constexpr int PW = Tile::kPerWave;
   if (total > 0) {
     int kv0;
     bool keep;
     chunk_of(0, kv0, keep);
-    DmaTile<D>::issue(plan, kb + (int64_t)kv0 * p.kv_st, sk[0], wave);
-    DmaTile<D>::issue(plan, vb + (int64_t)kv0 * p.kv_st, sv[0], wave);
+    Tile::issue(plan, kb + (int64_t)kv0 * p.kv_st, sk[0], wave);
+    Tile::issue(plan, vb + (int64_t)kv0 * p.kv_st, sv[0], wave);
   }
   wait_all_loads();
   __syncthreads();
@@ -129,10 +128,10 @@ __global__ __launch_bounds__(kThreads, (QT == 1 ? 2 : 1)) void fwd_kernel(const 
     int kv0;
     bool keep;
     chunk_of(it, kv0, keep);
-    // The next chunk's direct loads are spread between the MFMAs of the first contraction (the
-    // address unit takes a load every ~16 cycles, an MFMA 32), or issued at once by a wavefront
-    // that has nothing to compute for this chunk.
+    // The next step's direct loads are spread between the MFMAs of the first contraction, or
+    // issued at once by a wavefront that has nothing to compute in this step.
     const bool prefetch = it + 1 < total;
+    // nothing to do when my mask row drops the block or all keys lie after every one of my queries
     const bool compute = wave_active && keep && kv0 <= qw0 + MW - 1;
     const uint16_t* kg = kb;
     const uint16_t* vg = vb;
@@ -142,92 +141,78 @@ __global__ __launch_bounds__(kThreads, (QT == 1 ? 2 : 1)) void fwd_kernel(const 
       kg = kb + (int64_t)kv1 * p.kv_st;
       vg = vb + (int64_t)kv1 * p.kv_st;
       if (!compute) {
-        DmaTile<D>::issue(plan, kg, kn, wave);
-        DmaTile<D>::issue(plan, vg, vn, wave);
+        Tile::issue(plan, kg, kn, wave);
+        Tile::issue(plan, vg, vn, wave);
       }
     }
 
-    // keys of this chunk all lie after every one of my queries -> nothing to do
     if (compute) {
-      f32x16 s[QT][2];
+      f32x16 s[KT];
 #pragma unroll
-      for (int qt = 0; qt < QT; ++qt) s[qt][0] = s[qt][1] = f32x16{};
-      // all K fragments of the chunk are requested before the first MFMA needs one
-      bf16x8 kfr[2][D / 16];
-#pragma unroll
-      for (int kk = 0; kk < D / 16; ++kk)
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt) kfr[kt][kk] = DmaTile<D>::row_frag(ks, kt, kk, l32, half);
+      for (int kt = 0; kt < KT; ++kt) s[kt] = f32x16{};
+      // all K fragments of the step are requested before the first MFMA needs one
+      bf16x8 kfr[KT][D / 16];
 #pragma unroll
       for (int kk = 0; kk < D / 16; ++kk)
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
+        for (int kt = 0; kt < KT; ++kt) kfr[kt][kk] = Tile::row_frag(ks, kt, kk, l32, half);
 #pragma unroll
-          for (int qt = 0; qt < QT; ++qt) s[qt][kt] = mfma32(kfr[kt][kk], qf[qt][kk], s[qt][kt]);
-          constexpr int PW = DmaTile<D>::kPerWave;
-          const int n = 2 * kk + kt;
-          if (prefetch && n < PW) DmaTile<D>::issue_one(plan, n, kg, kn, wave);
-          if (prefetch && n >= PW && n < 2 * PW) DmaTile<D>::issue_one(plan, n - PW, vg, vn, wave);
+      for (int kk = 0; kk < D / 16; ++kk)
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) {
+          s[kt] = mfma32(kfr[kt][kk], qf[kk], s[kt]);
+          const int n = KT * kk + kt;
+          if (prefetch && n < PW) Tile::issue_one(plan, n, kg, kn, wave);
+          if (prefetch && n >= PW && n < 2 * PW) Tile::issue_one(plan, n - PW, vg, vn, wave);
         }
-      bf16x8 pb[QT][2][2];
+      static_assert(2 * PW <= KT * (D / 16), "every load has an MFMA to follow");
+      if (kv0 + CH - 1 > qw0) {  // diagonal: key position must not exceed query position
+        const int qpos = qw0 + l32;
 #pragma unroll
-      for (int qt = 0; qt < QT; ++qt) {
-        const int q0 = qw0 + 32 * qt;
-        if (kv0 + kChunk - 1 > q0) {  // diagonal: key position must not exceed query position
-          const int qpos = q0 + l32;
-#pragma unroll
-          for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const int key = kv0 + 32 * kt + 8 * (r >> 2) + 4 * half + (r & 3);
-              if (key > qpos) s[qt][kt][r] = kNegInf;
-            }
-        }
-        float mx = s[qt][0][0];
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[qt][kt][r]);
-        mx = max_halves(mx);
-        // a sub-tile wholly above the diagonal has mx = -inf; keep the running max unchanged then
-        const float m_new = fmaxf(m_run[qt], mx);
-        const float m_use = (m_new == kNegInf) ? 0.f : m_new;
-        const float alpha = fast_exp2((m_run[qt] - m_use) * c);
-        const float mc = m_use * c;
-        float psum = 0.f;
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
+        for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            s[qt][kt][r] = fast_exp2(__builtin_fmaf(s[qt][kt][r], c, -mc));
-            psum += s[qt][kt][r];
+            const int key = kv0 + 32 * kt + 8 * (r >> 2) + 4 * half + (r & 3);
+            if (key > qpos) s[kt][r] = kNegInf;
           }
-        l_run[qt] = l_run[qt] * alpha + psum;
-        if (__any(m_new != m_run[qt])) {
+      }
+      float mx = s[0][0];
+#pragma unroll
+      for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
+      mx = max_halves(mx);
+      // a tile wholly above the diagonal has mx = -inf; keep the running max unchanged then
+      const float m_new = fmaxf(m_run, mx);
+      const float m_use = (m_new == kNegInf) ? 0.f : m_new;
+      const float alpha = fast_exp2((m_run - m_use) * c);
+      const float mc = m_use * c;
+      float psum = 0.f;
+#pragma unroll
+      for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          s[kt][r] = fast_exp2(__builtin_fmaf(s[kt][r], c, -mc));
+          psum += s[kt][r];
+        }
+      l_run = l_run * alpha + psum;
+      if (__any(m_new != m_run)) {
+#pragma unroll
+        for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc_o[dt][r] *= alpha;
+      }
+      m_run = m_new;
+#pragma unroll
+      for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const bf16x8 pb = pack8(s[kt][8 * u + 0], s[kt][8 * u + 1], s[kt][8 * u + 2], s[kt][8 * u + 3],
+                                  s[kt][8 * u + 4], s[kt][8 * u + 5], s[kt][8 * u + 6], s[kt][8 * u + 7]);
 #pragma unroll
           for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc_o[qt][dt][r] *= alpha;
+            acc_o[dt] = mfma32(Tile::tr_frag(vs, dt, 2 * kt + u, trb), pb, acc_o[dt]);
         }
-        m_run[qt] = m_new;
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-          for (int u = 0; u < 2; ++u)
-            pb[qt][kt][u] = pack8(s[qt][kt][8 * u + 0], s[qt][kt][8 * u + 1], s[qt][kt][8 * u + 2],
-                                  s[qt][kt][8 * u + 3], s[qt][kt][8 * u + 4], s[qt][kt][8 * u + 5],
-                                  s[qt][kt][8 * u + 6], s[qt][kt][8 * u + 7]);
-      }
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-          for (int dt = 0; dt < D / 32; ++dt) {
-            const bf16x8 a = DmaTile<D>::tr_frag(vs, dt, 2 * kt + u, trb);
-#pragma unroll
-            for (int qt = 0; qt < QT; ++qt) acc_o[qt][dt] = mfma32(a, pb[qt][kt][u], acc_o[qt][dt]);
-          }
     }
 
     wait_all_loads();
@@ -235,40 +220,35 @@ __global__ __launch_bounds__(kThreads, (QT == 1 ? 2 : 1)) void fwd_kernel(const 
   }
 
   if (!wave_active) return;
+  const float l_tot = sum_halves(l_run);
+  const float inv = 1.0f / l_tot;
+  const int qrow = qw0 + l32;
+  uint16_t* orow = p.o + b * p.q_sb + h * p.q_sh + (int64_t)qrow * p.q_st;
 #pragma unroll
-  for (int qt = 0; qt < QT; ++qt) {
-    const float l_tot = sum_halves(l_run[qt]);
-    const float inv = 1.0f / l_tot;
-    const int qrow = qw0 + 32 * qt + l32;
-    uint16_t* orow = p.o + b * p.q_sb + h * p.q_sh + (int64_t)qrow * p.q_st;
+  for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt)
+    for (int g = 0; g < 4; ++g) {
+      bf16x4 w;
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        bf16x4 w;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) w[e] = (__bf16)(acc_o[qt][dt][4 * g + e] * inv);
-        *reinterpret_cast<bf16x4*>(orow + 32 * dt + 8 * g + 4 * half) = w;
-      }
-    if (half == 0) p.lse[((int64_t)b * p.heads + h) * N + qrow] = m_run[qt] * p.scale + __logf(l_tot);
-  }
+      for (int e = 0; e < 4; ++e) w[e] = (__bf16)(acc_o[dt][4 * g + e] * inv);
+      *reinterpret_cast<bf16x4*>(orow + 32 * dt + 8 * g + 4 * half) = w;
+    }
+  if (half == 0) p.lse[((int64_t)b * p.heads + h) * N + qrow] = m_run * p.scale + __logf(l_tot);
 }
 
-template <int D, bool DENSE, int QT>
+template <int D, bool DENSE>
 hipError_t launch_one(const AttnParams& p, hipStream_t stream) {
   const int T = p.fwd_tiles.tiles_per_head;
   const int grid = grid_for(p.batch * p.heads, T);
-  hipLaunchKernelGGL((fwd_kernel<D, DENSE, QT>), dim3(grid), dim3(kThreads), 0, stream, p);
+  hipLaunchKernelGGL((fwd_kernel<D, DENSE, kFwdChunk>), dim3(grid), dim3(kThreads), 0, stream, p);
   return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_fwd(const AttnParams& p, bool dense, hipStream_t stream) {
-  constexpr int QT = kFwdBM / 128;
-  if (p.head_dim == 128)
-    return dense ? launch_one<128, true, QT>(p, stream) : launch_one<128, false, QT>(p, stream);
-  return dense ? launch_one<64, true, QT>(p, stream) : launch_one<64, false, QT>(p, stream);
+  if (p.head_dim == 128) return dense ? launch_one<128, true>(p, stream) : launch_one<128, false>(p, stream);
+  return dense ? launch_one<64, true>(p, stream) : launch_one<64, false>(p, stream);
 }
 
 }  // namespace s2
