@@ -79,7 +79,8 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
   const int b = bh / p.heads, h = bh - b * p.heads;
   const int tile = DENSE ? (T - 1 - rank) : p.q_tiles.order[h * T + rank];
   const int S = DENSE ? kChunk : p.block_size;
-  const int cpb = S / kChunk;
+  const int cpb = S / kChunk;  // a power of two: / and % below are a shift and a mask
+  const int cpb_sh = __builtin_ctz(cpb), cpb_m = cpb - 1;
   const int N = p.seqlen;
   const int qw0 = tile * kBwdBM + wave * 32;
   const bool wave_active = qw0 < N;
@@ -106,8 +107,8 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
       kv0 = it * kChunk;
       keep = true;
     } else {
-      const int e = list.get(it / cpb, lane);
-      kv0 = (e >> 8) * S + (it % cpb) * kChunk;
+      const int e = list.get((it >> cpb_sh), lane);
+      kv0 = (e >> 8) * S + ((it & cpb_m)) * kChunk;
       keep = (e >> my_member) & 1;
     }
   };
@@ -116,8 +117,8 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
     if (DENSE) {
       kv0_n = (it + 1) * kChunk;
     } else {
-      const int e = (it + 1) / cpb == it / cpb ? list.get(it / cpb, lane) : list.peek_next(it / cpb);
-      kv0_n = (e >> 8) * S + ((it + 1) % cpb) * kChunk;
+      const int e = ((it + 1) >> cpb_sh) == (it >> cpb_sh) ? list.get((it >> cpb_sh), lane) : list.peek_next((it >> cpb_sh));
+      kv0_n = (e >> 8) * S + (((it + 1) & cpb_m)) * kChunk;
     }
   };
 
@@ -249,7 +250,8 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
   const int b = bh / p.heads, h = bh - b * p.heads;
   const int tile = DENSE ? rank : p.kv_tiles.order[h * T + rank];  // dense: first key tiles are longest
   const int S = DENSE ? kChunk : p.block_size;
-  const int cpb = S / kChunk;
+  const int cpb = S / kChunk;  // a power of two: / and % below are a shift and a mask
+  const int cpb_sh = __builtin_ctz(cpb), cpb_m = cpb - 1;
   const int N = p.seqlen;
 
   // my 32 key rows
@@ -288,8 +290,8 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
       q0 = N - kChunk - it * kChunk;  // from the last query chunk down, like the sparse lists
       keep = true;
     } else {
-      const int e = list.get(it / cpb, lane);
-      q0 = (e >> 8) * S + (cpb - 1 - it % cpb) * kChunk;
+      const int e = list.get((it >> cpb_sh), lane);
+      q0 = (e >> 8) * S + (cpb - 1 - (it & cpb_m)) * kChunk;
       keep = (e >> my_member) & 1;
     }
   };
@@ -298,8 +300,8 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
     if (DENSE) {
       q0_n = N - kChunk - (it + 1) * kChunk;
     } else {
-      const int e = (it + 1) / cpb == it / cpb ? list.get(it / cpb, lane) : list.peek_next(it / cpb);
-      q0_n = (e >> 8) * S + (cpb - 1 - (it + 1) % cpb) * kChunk;
+      const int e = ((it + 1) >> cpb_sh) == (it >> cpb_sh) ? list.get((it >> cpb_sh), lane) : list.peek_next((it >> cpb_sh));
+      q0_n = (e >> 8) * S + (cpb - 1 - ((it + 1) & cpb_m)) * kChunk;
     }
   };
 

@@ -47,7 +47,8 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
   const int b = bh / p.heads, h = bh - b * p.heads;
   const int tile = DENSE ? (T - 1 - rank) : p.fwd_tiles.order[h * T + rank];
   const int S = DENSE ? kChunk : p.block_size;
-  const int cpb = S / CH;  // steps per mask block
+  const int cpb = S / CH;  // steps per mask block: a power of two, so / and % below are a shift and a mask
+  const int cpb_sh = __builtin_ctz(cpb), cpb_m = cpb - 1;
 
   const int N = p.seqlen;
   const int qw0 = tile * BM + wave * MW;  // first query row of this wavefront
@@ -85,8 +86,8 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
       kv0 = it * CH;
       keep = true;
     } else {
-      const int e = list.get(it / cpb, lane);
-      kv0 = (e >> 8) * S + (it % cpb) * CH;
+      const int e = list.get((it >> cpb_sh), lane);
+      kv0 = (e >> 8) * S + ((it & cpb_m)) * CH;
       keep = (e >> my_member) & 1;
     }
   };
@@ -95,8 +96,8 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
     if (DENSE) {
       kv0_n = (it + 1) * CH;
     } else {
-      const int e = (it + 1) / cpb == it / cpb ? list.get(it / cpb, lane) : list.peek_next(it / cpb);
-      kv0_n = (e >> 8) * S + ((it + 1) % cpb) * CH;
+      const int e = ((it + 1) >> cpb_sh) == (it >> cpb_sh) ? list.get((it >> cpb_sh), lane) : list.peek_next((it >> cpb_sh));
+      kv0_n = (e >> 8) * S + (((it + 1) & cpb_m)) * CH;
     }
   };
 
@@ -129,21 +130,18 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
     bool keep;
     chunk_of(it, kv0, keep);
     // The next step's direct loads are spread between the MFMAs of the first contraction, or
-    // issued at once by a wavefront that has nothing to compute in this step.
-    const bool prefetch = it + 1 < total;
+    // issued at once by a wavefront that has nothing to compute in this step.  The last step
+    // loads its own chunk once more into the idle stage: nothing reads it, and the loop body
+    // then has no branch between the MFMAs.
     // nothing to do when my mask row drops the block or all keys lie after every one of my queries
     const bool compute = wave_active && keep && kv0 <= qw0 + MW - 1;
-    const uint16_t* kg = kb;
-    const uint16_t* vg = vb;
-    if (prefetch) {
-      int kv1;
-      next_chunk_of(it, kv1);
-      kg = kb + (int64_t)kv1 * p.kv_st;
-      vg = vb + (int64_t)kv1 * p.kv_st;
-      if (!compute) {
-        Tile::issue(plan, kg, kn, wave);
-        Tile::issue(plan, vg, vn, wave);
-      }
+    int kv1 = kv0;
+    if (it + 1 < total) next_chunk_of(it, kv1);
+    const uint16_t* kg = kb + (int64_t)kv1 * p.kv_st;
+    const uint16_t* vg = vb + (int64_t)kv1 * p.kv_st;
+    if (!compute) {
+      Tile::issue(plan, kg, kn, wave);
+      Tile::issue(plan, vg, vn, wave);
     }
 
     if (compute) {
@@ -162,8 +160,8 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
         for (int kt = 0; kt < KT; ++kt) {
           s[kt] = mfma32(kfr[kt][kk], qf[kk], s[kt]);
           const int n = KT * kk + kt;
-          if (prefetch && n < PW) Tile::issue_one(plan, n, kg, kn, wave);
-          if (prefetch && n >= PW && n < 2 * PW) Tile::issue_one(plan, n - PW, vg, vn, wave);
+          if (n < PW) Tile::issue_one(plan, n, kg, kn, wave);
+          if (n >= PW && n < 2 * PW) Tile::issue_one(plan, n - PW, vg, vn, wave);
         }
       static_assert(2 * PW <= KT * (D / 16), "every load has an MFMA to follow");
       if (kv0 + CH - 1 > qw0) {  // diagonal: key position must not exceed query position
