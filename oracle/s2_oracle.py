@@ -22,6 +22,9 @@ What each function follows:
   kept keys only (section 3.2) and its analytic gradient.
 * ``decode_row`` - one decoding step against a cache (section 4.1): the last
   row of the same masked attention.
+* ``resident_blocks`` / ``paged_decode_row`` - section 4.1's KV-efficient
+  cache: which blocks some later query can still attend (the rest may be
+  evicted), and decoding against a cache stored as pages behind a block table.
 
 Readings taken where the paper is silent (each is also listed in the design
 notes): the local case is restricted to j <= i (causal); the head offset is
@@ -308,3 +311,77 @@ def decode_row(q, k_cache, v_cache, length, global_head, block_size, local_block
     e = np.exp(z - m)
     l = e.sum()
     return (e / l) @ v, m + np.log(l)
+
+
+# ---------------------------------------------------------------------------------------------
+# Paged KV cache with block-aligned eviction (section 4.1)
+# ---------------------------------------------------------------------------------------------
+
+def resident_blocks(length, global_head, block_size, local_blocks, stride, window_blocks=0,
+                    dense=False):
+    """Logical KV blocks of one head that must stay cached once `length` tokens are cached.
+
+    Section 4.1: a KV block may be evicted as soon as no later query can attend to
+    it.  Written out as that definition: block j (among the ceil(L/S) blocks that
+    exist) stays iff SOME query block row i' >= (L-1) div S keeps it.  The scan
+    over future rows stops where the predicate has become constant in i' for
+    every j: the local case ends after B_l rows, the stripe case is constant once
+    i'-j >= B_l until the window (if any) ends.  Returns an ascending list.
+    """
+    L = int(length)
+    B = -(-L // block_size)
+    i = (L - 1) // block_size
+    if dense:
+        return list(range(B))
+    o_h = head_offset(global_head, stride)
+    horizon = local_blocks + window_blocks + max(stride, 1) + 2
+    keep = []
+    for j in range(B):
+        if any(block_predicate(ip, j, o_h, local_blocks, stride, window_blocks)
+               for ip in range(i, i + horizon)):
+            keep.append(j)
+    return keep
+
+
+def gather_pages(pages, table_row, n_blocks, block_size):
+    """Logical cache [n_blocks*S, D] of one (sequence, head) from a page pool.
+
+    pages [num_pages, S, D]; table_row[j] = page holding logical block j, or a
+    negative number if the block is not resident.  Blocks that are not resident
+    come back as NaN, so that any use of an evicted block shows in the result.
+    """
+    S = block_size
+    D = pages.shape[-1]
+    out = np.full((n_blocks * S, D), np.nan, dtype=np.float64)
+    for j in range(n_blocks):
+        pg = int(table_row[j])
+        if pg >= 0:
+            out[j * S:(j + 1) * S] = _f64(pages[pg])
+    return out
+
+
+def paged_decode_row(q, k_pages, v_pages, table_row, length, global_head, block_size,
+                     local_blocks, stride, scale, window_blocks=0, dense=False):
+    """decode_row on the logical cache that the page table describes.
+
+    A paged cache is storage only: the result is by definition that of the
+    contiguous cache it represents.  Keys of blocks the mask drops are never
+    looked at (their score is -inf whatever they hold), so their being absent
+    (NaN here) changes nothing; an absent block that the mask keeps makes the
+    result NaN.
+    """
+    L = int(length)
+    B = -(-L // block_size)
+    k = gather_pages(k_pages, table_row, B, block_size)
+    v = gather_pages(v_pages, table_row, B, block_size)
+    # decode_row multiplies every cached row by q before masking; rows of absent, dropped blocks
+    # must not turn into NaN * 0 there, so they are zeroed exactly where the mask drops them
+    i = (L - 1) // block_size
+    o_h = head_offset(global_head, stride)
+    for j in range(B):
+        kept = (j <= i) if dense else block_predicate(i, j, o_h, local_blocks, stride, window_blocks)
+        if not kept:
+            k[j * block_size:(j + 1) * block_size] = 0.0
+            v[j * block_size:(j + 1) * block_size] = 0.0
+    return decode_row(q, k, v, L, global_head, block_size, local_blocks, stride, scale,
+                      window_blocks, dense)
