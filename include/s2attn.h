@@ -110,6 +110,30 @@ typedef struct {
   int64_t kv_stride_seq, kv_stride_head, kv_stride_tok; /* elements, multiples of 8          */
 } s2_decode_args;
 
+/* Decode against a PAGED cache (section 4.1: the cache is kept in fixed-size blocks behind a block
+ * table, and a head's blocks that no later query can attend are evicted).  A page holds the
+ * block_size tokens of one logical KV block of one (sequence, head); K and V pools use the same
+ * page numbers. */
+typedef struct {
+  const void* q;              /* DEVICE bf16 [nseq, heads, head_dim], contiguous             */
+  const void* k_pages;        /* DEVICE bf16, element (page,t,d) at page*sp + t*st + d       */
+  const void* v_pages;        /* DEVICE bf16, same strides                                   */
+  const int32_t* block_table; /* DEVICE int32 [nseq, heads, max_blocks]: page of logical
+                                 block j of (sequence, head), negative = not resident        */
+  const int32_t* seq_lens;    /* DEVICE int32 [nseq], each in [1, max_blocks*block_size]     */
+  void* o;                    /* DEVICE bf16 [nseq, heads, head_dim], out                    */
+  float* lse;                 /* DEVICE fp32 [nseq, heads], out (may be NULL)                */
+  int32_t* missing;           /* DEVICE int32[1] or NULL: the call ADDS the number of
+                                 (sequence, head, block) triples the mask keeps but the
+                                 table does not hold (or holds with a page >= num_pages);
+                                 the caller zeroes it                                        */
+  int32_t nseq, heads, head_dim; /* head_dim 64 or 128                                       */
+  int32_t max_blocks;         /* row length of block_table; bounds seq_lens                  */
+  int32_t num_pages;          /* pages in each pool                                          */
+  int32_t num_splits;         /* KV splits per (sequence, head); 0 = library chooses         */
+  int64_t page_stride, tok_stride; /* elements, multiples of 8; tok_stride >= head_dim       */
+} s2_paged_decode_args;
+
 /* ---- layout (section 4.2 mask -> compressed lists, section 3.2) ------------------------- */
 
 /* Builds the per-head lists of kept KV blocks from the closed form of the mask, on the host,
@@ -168,6 +192,24 @@ size_t s2_attn_decode_workspace_bytes(int32_t nseq, int32_t heads, int32_t head_
                                       int32_t max_len, int32_t num_splits);
 /* The split count the library would pick for num_splits == 0. */
 int32_t s2_attn_decode_default_splits(int32_t nseq, int32_t heads, int32_t max_len);
+
+/* Same step against a paged cache.  A kept block whose table entry is negative (or not below
+ * num_pages) contributes nothing and is counted in *missing when that pointer is given; blocks
+ * the mask drops are never looked up, so their entries may hold anything.  A (sequence, head)
+ * all of whose kept blocks are missing gets o = 0 and lse = -inf.  Workspace as for
+ * s2_attn_decode with max_len = max_blocks * block_size.  Errors: NULL, BAD_PARAM, SHAPE, ALIGN,
+ * WORKSPACE, HIP. */
+int s2_attn_decode_paged(const s2_layout_params* p, const s2_paged_decode_args* a, float scale,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* Host helper for the cache manager (section 4.1, KV-efficient sparsity): the logical KV blocks
+ * of local head `head` that some query at position >= length-1 can still attend once `length`
+ * tokens are cached; every other block of that head may be evicted for good.  Writes them in
+ * ascending order to blocks[0..capacity) (HOST memory, may be NULL when capacity is 0) and the
+ * full count to *count.  Errors: NULL, BAD_PARAM (also head outside [0, num_heads), length < 1),
+ * OVERFLOW when capacity is too small (count is still set). */
+int s2_kv_resident_blocks(const s2_layout_params* p, int32_t head, int32_t length,
+                          int32_t* blocks, int32_t capacity, int32_t* count);
 
 /* ---- diagnostics -------------------------------------------------------------------------- */
 

@@ -63,10 +63,20 @@ class DecodeArgs(C.Structure):
                 ("kv_stride_seq", C.c_int64), ("kv_stride_head", C.c_int64), ("kv_stride_tok", C.c_int64)]
 
 
+class PagedDecodeArgs(C.Structure):
+    _fields_ = [("q", C.c_void_p), ("k_pages", C.c_void_p), ("v_pages", C.c_void_p),
+                ("block_table", C.c_void_p), ("seq_lens", C.c_void_p), ("o", C.c_void_p),
+                ("lse", C.c_void_p), ("missing", C.c_void_p),
+                ("nseq", C.c_int32), ("heads", C.c_int32), ("head_dim", C.c_int32),
+                ("max_blocks", C.c_int32), ("num_pages", C.c_int32), ("num_splits", C.c_int32),
+                ("page_stride", C.c_int64), ("tok_stride", C.c_int64)]
+
+
 EXPORTS = (
     "s2_layout_build", "s2_layout_destroy", "s2_layout_get", "s2_attn_fwd", "s2_attn_bwd",
     "s2_attn_bwd_workspace_bytes", "s2_attn_bwd_stages", "s2_dense_causal_fwd", "s2_dense_causal_bwd", "s2_attn_decode",
-    "s2_attn_decode_workspace_bytes", "s2_attn_decode_default_splits", "s2_status_string",
+    "s2_attn_decode_workspace_bytes", "s2_attn_decode_default_splits", "s2_attn_decode_paged",
+    "s2_kv_resident_blocks", "s2_status_string",
     "s2_last_hip_error", "s2_version",
 )
 
@@ -98,6 +108,10 @@ def lib():
     L.s2_attn_decode_workspace_bytes.restype = C.c_size_t
     L.s2_attn_decode_default_splits.argtypes = [C.c_int32] * 3
     L.s2_attn_decode_default_splits.restype = C.c_int32
+    L.s2_attn_decode_paged.argtypes = [C.POINTER(LayoutParams), C.POINTER(PagedDecodeArgs), C.c_float,
+                                       C.c_void_p, C.c_size_t, C.c_void_p]
+    L.s2_kv_resident_blocks.argtypes = [C.POINTER(LayoutParams), C.c_int32, C.c_int32,
+                                        C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_int32)]
     L.s2_status_string.argtypes = [C.c_int]
     L.s2_status_string.restype = C.c_char_p
     L.s2_last_hip_error.restype = C.c_int
@@ -246,3 +260,30 @@ def s2_attn_decode(params, q, k_cache, v_cache, seq_lens, o, lse, scale, workspa
     _check(lib().s2_attn_decode(C.byref(params), C.byref(a), scale, _ptr(workspace),
                                 workspace.numel() * workspace.element_size(), _stream_ptr(stream)),
            "s2_attn_decode")
+
+
+def s2_attn_decode_paged(params, q, k_pages, v_pages, block_table, seq_lens, o, lse, scale, workspace,
+                         missing=None, num_splits=0, stream=None):
+    """k_pages, v_pages: [num_pages, block_size, head_dim]; block_table: int32 [nseq, heads, max_blocks]."""
+    nseq, H, D = q.shape
+    assert q.is_contiguous() and o.is_contiguous() and block_table.is_contiguous()
+    assert k_pages.stride() == v_pages.stride() and k_pages.stride(2) == 1
+    assert tuple(block_table.shape[:2]) == (nseq, H)
+    a = PagedDecodeArgs(_ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(block_table), _ptr(seq_lens), _ptr(o),
+                        _ptr(lse), _ptr(missing), nseq, H, D, block_table.shape[2], k_pages.shape[0],
+                        num_splits, k_pages.stride(0), k_pages.stride(1))
+    _check(lib().s2_attn_decode_paged(C.byref(params), C.byref(a), scale, _ptr(workspace),
+                                      workspace.numel() * workspace.element_size(), _stream_ptr(stream)),
+           "s2_attn_decode_paged")
+
+
+def s2_kv_resident_blocks(params, head, length):
+    """Ascending list of the logical KV blocks local head `head` still needs with `length` tokens cached."""
+    n = C.c_int32(0)
+    st = lib().s2_kv_resident_blocks(C.byref(params), head, length, None, 0, C.byref(n))
+    if st not in (0, -8):
+        _check(st, "s2_kv_resident_blocks")
+    buf = (C.c_int32 * max(1, n.value))()
+    _check(lib().s2_kv_resident_blocks(C.byref(params), head, length, buf, n.value, C.byref(n)),
+           "s2_kv_resident_blocks")
+    return list(buf[:n.value])

@@ -4,6 +4,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <limits>
 #include <new>
 
 #include "../../include/s2attn.h"
@@ -342,6 +343,86 @@ int s2_attn_decode(const s2_layout_params* lp, const s2_decode_args* a, float sc
   p.dense = lp->dense;
   p.head_index_base = lp->head_index_base;
   return hip_ok(s2::launch_decode(p, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
+}
+
+int s2_attn_decode_paged(const s2_layout_params* lp, const s2_paged_decode_args* a, float scale,
+                         void* workspace, size_t workspace_bytes, void* stream) {
+  if (!lp || !a) return S2_ERR_NULL;
+  if (!a->q || !a->k_pages || !a->v_pages || !a->block_table || !a->seq_lens || !a->o) return S2_ERR_NULL;
+  if (!(scale > 0.f) || !std::isfinite(scale)) return S2_ERR_BAD_PARAM;
+  if (lp->block_size != 64 && lp->block_size != 128) return S2_ERR_BAD_PARAM;
+  if (lp->dense != 0 && lp->dense != 1) return S2_ERR_BAD_PARAM;
+  if (!lp->dense && (lp->local_blocks < 1 || lp->stride < 0 || lp->window_blocks < 0)) return S2_ERR_BAD_PARAM;
+  if (lp->head_index_base < 0) return S2_ERR_BAD_PARAM;
+  if (a->nseq < 1 || a->heads < 1 || a->max_blocks < 1 || a->num_pages < 1) return S2_ERR_SHAPE;
+  if ((int64_t)a->max_blocks * lp->block_size > std::numeric_limits<int32_t>::max()) return S2_ERR_SHAPE;
+  if (a->heads != lp->num_heads) return S2_ERR_SHAPE;
+  if (a->head_dim != 64 && a->head_dim != 128) return S2_ERR_SHAPE;
+  if (a->num_splits < 0 || a->num_splits > 64) return S2_ERR_BAD_PARAM;
+  if (a->page_stride < 0 || (a->page_stride & 7) != 0 || a->tok_stride < 0 || (a->tok_stride & 7) != 0)
+    return S2_ERR_ALIGN;
+  if (a->tok_stride < a->head_dim) return S2_ERR_ALIGN;
+  if (!aligned16(a->q) || !aligned16(a->k_pages) || !aligned16(a->v_pages) || !aligned16(a->o) ||
+      (reinterpret_cast<uintptr_t>(a->seq_lens) & 3u) != 0 ||
+      (reinterpret_cast<uintptr_t>(a->block_table) & 3u) != 0 ||
+      (reinterpret_cast<uintptr_t>(a->missing) & 3u) != 0)
+    return S2_ERR_ALIGN;
+  const int max_len = a->max_blocks * lp->block_size;
+  const int splits = a->num_splits > 0 ? a->num_splits
+                                       : s2_attn_decode_default_splits(a->nseq, a->heads, max_len);
+  const size_t need = s2_attn_decode_workspace_bytes(a->nseq, a->heads, a->head_dim, max_len, splits);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || workspace_bytes < need)
+    return S2_ERR_WORKSPACE;
+
+  s2::DecodeParams p{};
+  p.q = static_cast<const uint16_t*>(a->q);
+  p.k_cache = static_cast<const uint16_t*>(a->k_pages);
+  p.v_cache = static_cast<const uint16_t*>(a->v_pages);
+  p.seq_lens = a->seq_lens;
+  p.o = static_cast<uint16_t*>(a->o);
+  p.lse = a->lse;
+  const size_t items = (size_t)a->nseq * a->heads * splits;
+  p.part_acc = static_cast<float*>(workspace);
+  p.part_ml = p.part_acc + items * a->head_dim;
+  p.nseq = a->nseq;
+  p.heads = a->heads;
+  p.head_dim = a->head_dim;
+  p.max_len = max_len;
+  p.num_splits = splits;
+  p.kv_ss = a->page_stride;
+  p.kv_sh = 0;
+  p.kv_st = a->tok_stride;
+  p.scale = scale;
+  p.scale_log2e = scale * 1.4426950408889634f;
+  p.block_size = lp->block_size;
+  p.local_blocks = lp->local_blocks;
+  p.stride = lp->stride;
+  p.window_blocks = lp->window_blocks;
+  p.dense = lp->dense;
+  p.head_index_base = lp->head_index_base;
+  p.block_table = a->block_table;
+  p.missing = a->missing;
+  p.max_blocks = a->max_blocks;
+  p.num_pages = a->num_pages;
+  return hip_ok(s2::launch_decode(p, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
+}
+
+int s2_kv_resident_blocks(const s2_layout_params* lp, int32_t head, int32_t length, int32_t* blocks,
+                          int32_t capacity, int32_t* count) {
+  if (!lp || !count) return S2_ERR_NULL;
+  if (capacity < 0 || (capacity > 0 && !blocks)) return S2_ERR_NULL;
+  if (lp->block_size != 64 && lp->block_size != 128) return S2_ERR_BAD_PARAM;
+  if (lp->dense != 0 && lp->dense != 1) return S2_ERR_BAD_PARAM;
+  if (!lp->dense && (lp->local_blocks < 1 || lp->stride < 0 || lp->window_blocks < 0)) return S2_ERR_BAD_PARAM;
+  if (lp->head_index_base < 0 || lp->num_heads < 1) return S2_ERR_BAD_PARAM;
+  if (head < 0 || head >= lp->num_heads || length < 1) return S2_ERR_BAD_PARAM;
+  // Every block a later row keeps among blocks 0..i is also kept by row i = (length-1) div S
+  // (the mask only loses columns as the row index grows: a local block drops out of the window,
+  // a stripe block stays until the optional window passes it), so the answer is row i itself.
+  const int i = (length - 1) / lp->block_size;
+  const int64_t n = s2::row_blocks(*lp, head, i, blocks, capacity);
+  *count = (int32_t)n;
+  return n > capacity ? S2_ERR_OVERFLOW : S2_OK;
 }
 
 const char* s2_status_string(int status) {

@@ -5,6 +5,9 @@
 // issues 16-byte loads, a row of K or V is covered by D/8 adjacent lanes, and both the K and V
 // loads of a 64-token unit are in flight before the first score is needed.
 //
+// Paged cache (PAGED = true): a kept block's rows are found through the block table instead of
+// by offset into a contiguous cache; nothing else changes, since a page is one contiguous block.
+//
 // Split-KV: the list of 64-token units of one (sequence, head) is cut into num_splits pieces, one
 // workgroup each; the four wavefronts of a workgroup take units round-robin and merge their
 // (max, sum, accumulator) through LDS; a second kernel merges the splits.
@@ -53,7 +56,7 @@ __device__ inline RowBlocks row_blocks(const DecodeParams& p, int head, int i) {
   return r;
 }
 
-template <int D>
+template <int D, bool PAGED>
 __global__ __launch_bounds__(256, 2) void decode_split_kernel(const DecodeParams p) {
   constexpr int LPR = D / 8;     // lanes covering one row
   constexpr int RPI = 64 / LPR;  // rows covered by one wavefront-wide load
@@ -71,6 +74,7 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(const DecodeParams
 
   int L = p.seq_lens[b];
   L = min(max(L, 1), p.max_len);
+  const int32_t* table = PAGED ? p.block_table + ((int64_t)b * p.heads + h) * p.max_blocks : nullptr;
   const int S = p.block_size;
   const int cpb = S / kChunk;
   const int i = (L - 1) / S;
@@ -86,8 +90,9 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(const DecodeParams
 #pragma unroll
     for (int e = 0; e < 8; ++e) qv[e] = (float)q8[e];
   }
-  const uint16_t* kb = p.k_cache + b * p.kv_ss + h * p.kv_sh + 8 * c;
-  const uint16_t* vb = p.v_cache + b * p.kv_ss + h * p.kv_sh + 8 * c;
+  const uint16_t* kb = p.k_cache + (PAGED ? 0 : b * p.kv_ss + h * p.kv_sh) + 8 * c;
+  const uint16_t* vb = p.v_cache + (PAGED ? 0 : b * p.kv_ss + h * p.kv_sh) + 8 * c;
+  int n_missing = 0;
   const float cl = p.scale_log2e;
 
   float m_run = kNegInf, l_run = 0.f;
@@ -96,18 +101,31 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(const DecodeParams
   for (int e = 0; e < 8; ++e) acc[e] = 0.f;
 
   for (int u = u_lo + wave; u < u_hi; u += 4) {
-    const int tok0 = rb.block(u / cpb) * S + (u % cpb) * kChunk;
+    const int blk = rb.block(u / cpb);
+    const int tok0 = blk * S + (u % cpb) * kChunk;
     if (tok0 >= L) continue;  // second half of a partial last block
+    // row `tok` of the cache is at base + (tok - shift) * kv_st
+    int64_t base = 0;
+    int shift = 0;
+    if (PAGED) {
+      const int page = table[blk];
+      if (page < 0 || page >= p.num_pages) {  // kept by the mask but not resident
+        n_missing += (u % cpb) == 0;
+        continue;
+      }
+      base = (int64_t)page * p.kv_ss;
+      shift = blk * S;
+    }
     bf16x8 kr[NI], vr[NI];
 #pragma unroll
     for (int n = 0; n < NI; ++n) {
       const int tok = min(tok0 + RPI * n + g, L - 1);  // clamp: never read past the sequence
-      kr[n] = *reinterpret_cast<const bf16x8*>(kb + (int64_t)tok * p.kv_st);
+      kr[n] = *reinterpret_cast<const bf16x8*>(kb + base + (int64_t)(tok - shift) * p.kv_st);
     }
 #pragma unroll
     for (int n = 0; n < NI; ++n) {
       const int tok = min(tok0 + RPI * n + g, L - 1);
-      vr[n] = *reinterpret_cast<const bf16x8*>(vb + (int64_t)tok * p.kv_st);
+      vr[n] = *reinterpret_cast<const bf16x8*>(vb + base + (int64_t)(tok - shift) * p.kv_st);
     }
     float s[NI];
     float mx = kNegInf;
@@ -140,6 +158,8 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(const DecodeParams
     l_run = l_run * alpha + psum;  // per row group; groups are summed at the end
     m_run = m_new;
   }
+
+  if (PAGED && p.missing && lane == 0 && n_missing > 0) atomicAdd(p.missing, n_missing);
 
   // sum the row groups of the wavefront
 #pragma unroll
@@ -191,15 +211,19 @@ __global__ __launch_bounds__(D) void decode_reduce_kernel(const DecodeParams p) 
     l += ml[2 * s + 1] * wgt;
     a += p.part_acc[((int64_t)bh * p.num_splits + s) * D + d] * wgt;
   }
-  const __bf16 out = (__bf16)(a / l);
+  // l == 0 only when nothing was attended: a paged cache with every kept block missing
+  const __bf16 out = (__bf16)(l > 0.f ? a / l : 0.f);
   p.o[(int64_t)bh * D + d] = *reinterpret_cast<const uint16_t*>(&out);
-  if (d == 0 && p.lse) p.lse[bh] = m * p.scale + __logf(l);
+  if (d == 0 && p.lse) p.lse[bh] = l > 0.f ? m * p.scale + __logf(l) : kNegInf;
 }
 
 template <int D>
 hipError_t launch_one(const DecodeParams& p, hipStream_t stream) {
   const int bh = p.nseq * p.heads;
-  hipLaunchKernelGGL((decode_split_kernel<D>), dim3(bh * p.num_splits), dim3(256), 0, stream, p);
+  if (p.block_table)
+    hipLaunchKernelGGL((decode_split_kernel<D, true>), dim3(bh * p.num_splits), dim3(256), 0, stream, p);
+  else
+    hipLaunchKernelGGL((decode_split_kernel<D, false>), dim3(bh * p.num_splits), dim3(256), 0, stream, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((decode_reduce_kernel<D>), dim3(bh), dim3(D), 0, stream, p);

@@ -52,6 +52,10 @@ struct DecodeParams {
   int64_t kv_ss, kv_sh, kv_st;
   float scale, scale_log2e;
   int block_size, local_blocks, stride, window_blocks, dense, head_index_base;
+  // paged cache: k_cache / v_cache are the page pools, kv_ss is the page stride
+  const int32_t* block_table;  // [nseq, heads, max_blocks], nullptr = contiguous cache
+  int32_t* missing;            // optional counter of kept blocks that are not resident
+  int max_blocks, num_pages;
 };
 
 // Each returns the hipError_t of the launch (hipGetLastError after the launch).

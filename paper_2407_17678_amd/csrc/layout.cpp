@@ -55,6 +55,15 @@ inline void for_col(const s2_layout_params& p, int o, int j, F&& emit) {
 
 }  // namespace
 
+int64_t row_blocks(const s2_layout_params& p, int head, int i, int32_t* out, int64_t capacity) {
+  int64_t n = 0;
+  for_row(p, head_offset(p, head), i, [&](int j) {
+    if (n < capacity) out[n] = j;
+    ++n;
+  });
+  return n;
+}
+
 int build_host(const s2_layout_params& p, s2_layout& L) {
   if (p.num_heads < 1 || p.num_blocks < 1 || p.head_index_base < 0) return S2_ERR_BAD_PARAM;
   if (p.block_size != 64 && p.block_size != 128) return S2_ERR_BAD_PARAM;

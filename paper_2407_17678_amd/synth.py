@@ -106,3 +106,39 @@ def decode_inputs_small(w, nseq, heads, max_len, lengths=None):
     if lengths is None:
         lengths = rng.integers(max(1, max_len // 4), max_len + 1, size=nseq).astype(np.int32)
     return q, kc, vc, np.asarray(lengths, dtype=np.int32)
+
+
+def page_table(resident, max_blocks, extra_pages=3, seed_stream=3, index=0):
+    """Scatters resident blocks over a page pool.
+
+    resident[b][h] = list of logical block numbers of (sequence b, head h) that are held.  Returns
+    (table int32 [nseq, heads, max_blocks] with -1 for blocks not held, num_pages): every held
+    block gets its own page, pages handed out in a seeded random order, `extra_pages` pages left
+    unused.  Bookkeeping only; which blocks are held is the caller's business.
+    """
+    nseq, heads = len(resident), len(resident[0])
+    total = sum(len(r) for row in resident for r in row)
+    num_pages = total + extra_pages
+    order = rng_for(index, seed_stream).permutation(num_pages)
+    table = np.full((nseq, heads, max_blocks), -1, dtype=np.int32)
+    n = 0
+    for b in range(nseq):
+        for h in range(heads):
+            for j in resident[b][h]:
+                table[b, h, j] = order[n]
+                n += 1
+    return table, num_pages
+
+
+def pages_from_cache(cache_bits, table, num_pages, block_size):
+    """Page pool [num_pages, S, D] (bf16 bits) holding the blocks of a contiguous cache
+    [nseq, heads, max_len, D] that `table` marks as held; other pages get a recognisable filler."""
+    nseq, heads, max_len, D = cache_bits.shape
+    pool = np.full((num_pages, block_size, D), 0x7F00, dtype=np.uint16)  # large finite bf16 values
+    for b in range(nseq):
+        for h in range(heads):
+            for j in np.nonzero(table[b, h] >= 0)[0]:
+                lo = j * block_size
+                rows = cache_bits[b, h, lo:lo + block_size]
+                pool[table[b, h, j], :rows.shape[0]] = rows
+    return pool

@@ -171,3 +171,70 @@ def test_decode_argument_errors():
     need = lib.s2_attn_decode_workspace_bytes(3, 2, 128, 1000, 2)
     assert need >= 3 * 2 * 2 * 130 * 4
     assert 1 <= lib.s2_attn_decode_default_splits(64, 32, 32768) <= 64
+
+
+def test_resident_blocks_bit_exact_against_the_oracle():
+    # the cache manager's helper (which blocks a head may never evict) against the oracle's
+    # definition-by-scan, at the decode workload and at random parameters incl. windows
+    w = WORKLOADS["7b_decode"]
+    p = B.layout_params(w.heads, 1, w.block_size, w.local_blocks, w.stride, 0, w.window_blocks, 0)
+    for h in (0, 5, 15, 31):
+        for L in (1, 64, 65, 1024, 8192, 20001, 32768):
+            assert B.s2_kv_resident_blocks(p, h, L) == orc.resident_blocks(L, h, 64, w.local_blocks, w.stride)
+    rng = np.random.default_rng(5)
+    for _ in range(150):
+        S = int(rng.choice([64, 128]))
+        H = int(rng.integers(1, 9))
+        B_l = int(rng.integers(1, 7))
+        s = int(rng.integers(0, 9))
+        win = int(rng.choice([0, 0, rng.integers(B_l, 40)]))
+        base = int(rng.integers(0, 20))
+        dense = int(rng.integers(0, 8) == 0)
+        h = int(rng.integers(0, H))
+        L = int(rng.integers(1, 40 * S))
+        p = B.layout_params(H, 1, S, B_l, s, base, win, dense)
+        assert B.s2_kv_resident_blocks(p, h, L) == orc.resident_blocks(L, base + h, S, B_l, s, win, bool(dense))
+
+
+def test_resident_blocks_errors():
+    lib = B.lib()
+    p = B.layout_params(4, 1, 64, 2, 4)
+    n = C.c_int32(-1)
+    buf = (C.c_int32 * 2)()
+    assert lib.s2_kv_resident_blocks(None, 0, 10, buf, 2, C.byref(n)) == -1
+    assert lib.s2_kv_resident_blocks(C.byref(p), 0, 10, buf, 2, None) == -1
+    assert lib.s2_kv_resident_blocks(C.byref(p), 0, 10, None, 2, C.byref(n)) == -1
+    assert lib.s2_kv_resident_blocks(C.byref(p), 4, 10, buf, 2, C.byref(n)) == -2   # head out of range
+    assert lib.s2_kv_resident_blocks(C.byref(p), -1, 10, buf, 2, C.byref(n)) == -2
+    assert lib.s2_kv_resident_blocks(C.byref(p), 0, 0, buf, 2, C.byref(n)) == -2    # length < 1
+    bad = B.layout_params(4, 1, 32, 2, 4)
+    assert lib.s2_kv_resident_blocks(C.byref(bad), 0, 10, buf, 2, C.byref(n)) == -2
+    # capacity too small: count still reported, first entries written
+    assert lib.s2_kv_resident_blocks(C.byref(p), 0, 64 * 8, buf, 2, C.byref(n)) == -8
+    assert n.value == 4 and list(buf) == [0, 4]
+    assert lib.s2_kv_resident_blocks(C.byref(p), 0, 64 * 8, None, 0, C.byref(n)) == -8 and n.value == 4
+
+
+def test_paged_decode_argument_errors_without_launch():
+    lib = B.lib()
+    p = B.layout_params(2, 1, 64, 2, 4)
+    a = B.PagedDecodeArgs()
+    assert lib.s2_attn_decode_paged(None, C.byref(a), 1.0, None, 0, None) == -1
+    assert lib.s2_attn_decode_paged(C.byref(p), C.byref(a), 1.0, None, 0, None) == -1   # NULL tensors
+    for f in ("q", "k_pages", "v_pages", "block_table", "seq_lens", "o"):
+        setattr(a, f, 4096)
+    a.nseq, a.heads, a.head_dim, a.max_blocks, a.num_pages = 1, 2, 64, 4, 8
+    a.page_stride, a.tok_stride = 64 * 64, 64
+    assert lib.s2_attn_decode_paged(C.byref(p), C.byref(a), 0.0, None, 0, None) == -2   # scale
+    a.heads = 3
+    assert lib.s2_attn_decode_paged(C.byref(p), C.byref(a), 1.0, None, 0, None) == -3   # heads differ
+    a.heads, a.head_dim = 2, 96
+    assert lib.s2_attn_decode_paged(C.byref(p), C.byref(a), 1.0, None, 0, None) == -3
+    a.head_dim, a.tok_stride = 64, 60
+    assert lib.s2_attn_decode_paged(C.byref(p), C.byref(a), 1.0, None, 0, None) == -4   # stride
+    a.tok_stride, a.q = 64, 4100
+    assert lib.s2_attn_decode_paged(C.byref(p), C.byref(a), 1.0, None, 0, None) == -4   # alignment
+    a.q, a.num_splits = 4096, 65
+    assert lib.s2_attn_decode_paged(C.byref(p), C.byref(a), 1.0, None, 0, None) == -2
+    a.num_splits = 0
+    assert lib.s2_attn_decode_paged(C.byref(p), C.byref(a), 1.0, None, 0, None) == -5   # workspace
