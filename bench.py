@@ -210,6 +210,58 @@ def cpu_baseline_train(w, tensors, sample_tokens, with_bwd=True):
             "seconds": sec, "host_cores_visible": int(cores)}, parity
 
 
+def bench_decode_paged(w, steps, warmup):
+    """The decode workload with the cache held as pages behind a block table, each head keeping
+    only the blocks some later query can still attend (section 4.1)."""
+    import torch
+    from paper_2407_17678_amd import binding as B
+    from paper_2407_17678_amd import synth
+    nseq, H, D, max_len, S = w.batch, w.heads, w.head_dim, w.max_len, w.block_size
+    lens = synth.decode_lengths(w)
+    p = B.layout_params(H, 1, S, w.local_blocks, w.stride, 0, w.window_blocks, 0)
+    resident = [[B.s2_kv_resident_blocks(p, h, int(L)) for h in range(H)] for L in lens]
+    max_blocks = max_len // S
+    table, num_pages = synth.page_table(resident, max_blocks, index=w.index)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.BASE_SEED + w.index)
+    q = torch.randn((nseq, H, D), device="cuda", generator=gen).to(torch.bfloat16)
+    kp = torch.empty((num_pages, S, D), dtype=torch.bfloat16, device="cuda")
+    vp = torch.empty_like(kp)
+    step = 4096
+    for lo in range(0, num_pages, step):   # fill in slices so that the fp32 temporaries stay small
+        n = min(step, num_pages - lo)
+        kp[lo:lo + n] = torch.randn((n, S, D), device="cuda", generator=gen).to(torch.bfloat16)
+        vp[lo:lo + n] = torch.randn((n, S, D), device="cuda", generator=gen).to(torch.bfloat16)
+    tb = torch.from_numpy(table).cuda()
+    sl = torch.from_numpy(lens).cuda()
+    o = torch.empty_like(q)
+    lse = torch.empty((nseq, H), dtype=torch.float32, device="cuda")
+    missing = torch.zeros(1, dtype=torch.int32, device="cuda")
+    splits = B.s2_attn_decode_default_splits(nseq, H, max_len)
+    ws = torch.empty(B.s2_attn_decode_workspace_bytes(nseq, H, D, max_len, splits), dtype=torch.uint8,
+                     device="cuda")
+    run = lambda: B.s2_attn_decode_paged(p, q, kp, vp, tb, sl, o, lse, w.scale, ws, missing=missing,
+                                         num_splits=splits)
+    ms = time_events(run, steps, warmup)
+    if int(missing.item()) != 0:
+        sys.exit("bench.py: the paged decode found kept blocks missing from its own table")
+    tokens = 0
+    for b, L in enumerate(lens.tolist()):
+        i = (L - 1) // S
+        for h in range(H):
+            tokens += sum(min(S, L - j * S) for j in resident[b][h])
+            assert resident[b][h][-1] == i
+    kv_bytes = tokens * D * 2 * 2
+    # q, o, split partials, and the table entries looked up
+    other = nseq * H * D * 2 * 2 + 2 * nseq * H * splits * (D + 2) * 4 + sum(len(r) for row in resident for r in row) * 4
+    gbs = (kv_bytes + other) / (ms * 1e-3) / 1e9
+    contiguous_gb = 2 * nseq * H * max_len * D * 2 / 1e9
+    return dict(workload=w.name + "_paged", nseq=nseq, heads=H, head_dim=D, max_len=max_len, splits=int(splits),
+                mean_len=float(lens.mean()), ms=ms, kept_tokens=int(tokens), pages=int(num_pages),
+                cache_gb=2 * num_pages * S * D * 2 / 1e9, contiguous_cache_gb=contiguous_gb,
+                algorithmic_gb=(kv_bytes + other) / 1e9, hbm_gbs=gbs, frac_hbm_peak=gbs / PEAK_HBM_GBS)
+
+
 def bench_decode(w, steps, warmup):
     import torch
     from paper_2407_17678_amd import binding as B
@@ -257,7 +309,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="7b_32k", choices=["tiny", "1p3b_8k", "7b_32k", "7b_128k", "7b_decode"])
+    ap.add_argument("--workload", default="7b_32k", choices=["tiny", "1p3b_8k", "7b_32k", "7b_128k", "7b_decode", "7b_decode_paged"])
     ap.add_argument("--cpu-sample-tokens", type=int, default=32768)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
@@ -279,7 +331,8 @@ def main():
         sys.exit("bench.py: no GPU visible; the HIP library is the only path")
     B.lib()
     torch.cuda.set_device(0)
-    w = synth.WORKLOADS[args.workload]
+    paged = args.workload == "7b_decode_paged"
+    w = synth.WORKLOADS["7b_decode" if paged else args.workload]
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 255)
         dst = torch.empty_like(src)
@@ -289,14 +342,14 @@ def main():
         del src, dst
 
     if w.kind == "decode":
-        d = bench_decode(w, args.steps, args.warmup)
+        d = bench_decode_paged(w, args.steps, args.warmup) if paged else bench_decode(w, args.steps, args.warmup)
         out = {"metric": "decode HBM GB/s (algorithmic K+V bytes of kept blocks)", "value": d["hbm_gbs"],
                "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": d["ms"],
                "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
                "data": "synthetic", "config": d,
                "roofline": {"kernel": "decode_split_kernel", "bound": "hbm", "achieved": d["hbm_gbs"],
                             "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": d["frac_hbm_peak"],
-                            "traffic": measured_traffic(w.name, "decode_split_kernel")},
+                            "traffic": measured_traffic(d["workload"], "decode_split_kernel")},
                "cpu_baseline": None}
         print(json.dumps(out))
         return
@@ -327,6 +380,7 @@ def main():
             del t
             torch.cuda.empty_cache()
         extra["7b_decode"] = bench_decode(synth.WORKLOADS["7b_decode"], 20, 3)
+        extra["7b_decode_paged"] = bench_decode_paged(synth.WORKLOADS["7b_decode"], 20, 3)
 
     out = {
         "metric": "effective sparse-attn TFLOP/s fwd+bwd (% MFMA peak) + speedup vs dense causal"

@@ -123,3 +123,55 @@ def test_7b_decode_full():
                                       w.block_size, w.local_blocks, w.stride, w.scale)
         assert G.o_excess(G.to_f64(o[b, h]), ref) <= 0, (b, h)
         assert abs(float(lse[b, h]) - ref_lse) <= 1e-3, (b, h)
+
+
+def test_7b_decode_paged_full():
+    """The same 64 x 32 decode step with the cache as pages: each head holds only the blocks it can
+    still attend (about 1/9 of a contiguous cache).  The oracle checks a sample of (sequence, head)
+    pairs on their own pages copied back."""
+    w = synth.WORKLOADS["7b_decode"]
+    print("full-size case", w.name, "paged", flush=True)
+    nseq, H, D, max_len, S = w.batch, w.heads, w.head_dim, w.max_len, w.block_size
+    lens = synth.decode_lengths(w)
+    resident = [[orc.resident_blocks(int(L), h, S, w.local_blocks, w.stride) for h in range(H)] for L in lens]
+    max_blocks = max_len // S
+    table, num_pages = synth.page_table(resident, max_blocks, index=w.index)
+    assert num_pages * S < 0.13 * nseq * H * max_len
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.BASE_SEED + w.index)
+    q = torch.randn((nseq, H, D), device="cuda", generator=gen).to(torch.bfloat16)
+    kp = torch.empty((num_pages, S, D), dtype=torch.bfloat16, device="cuda")
+    vp = torch.empty_like(kp)
+    for lo in range(0, num_pages, 4096):
+        n = min(4096, num_pages - lo)
+        kp[lo:lo + n] = torch.randn((n, S, D), device="cuda", generator=gen).to(torch.bfloat16)
+        vp[lo:lo + n] = torch.randn((n, S, D), device="cuda", generator=gen).to(torch.bfloat16)
+    tb = torch.from_numpy(table).cuda()
+    sl = torch.from_numpy(lens).cuda()
+    o = torch.empty_like(q)
+    lse = torch.empty((nseq, H), dtype=torch.float32, device="cuda")
+    missing = torch.zeros(1, dtype=torch.int32, device="cuda")
+    p = B.layout_params(H, 1, S, w.local_blocks, w.stride)
+    splits = B.s2_attn_decode_default_splits(nseq, H, max_len)
+    ws = torch.empty(B.s2_attn_decode_workspace_bytes(nseq, H, D, max_len, splits), dtype=torch.uint8,
+                     device="cuda")
+    B.s2_attn_decode_paged(p, q, kp, vp, tb, sl, o, lse, w.scale, ws, missing=missing, num_splits=splits)
+    torch.cuda.synchronize()
+    assert int(missing.item()) == 0
+    assert torch.isfinite(o.float()).all()
+    rng = np.random.default_rng(4)
+    pairs = {(int(np.argmin(lens)), 0), (int(np.argmax(lens)), 31)}
+    while len(pairs) < 24:
+        pairs.add((int(rng.integers(0, nseq)), int(rng.integers(0, H))))
+    for (b, h) in sorted(pairs):
+        L = int(lens[b])
+        # this pair's pages, renumbered 0..n-1
+        held = resident[b][h]
+        idx = torch.from_numpy(table[b, h, held].astype(np.int64)).cuda()
+        kpool, vpool = G.to_f64(kp[idx]), G.to_f64(vp[idx])
+        row = np.full(max_blocks, -1, dtype=np.int32)
+        row[held] = np.arange(len(held))
+        ref, ref_lse = orc.paged_decode_row(G.to_f64(q[b, h]), kpool, vpool, row, L, h, S, w.local_blocks,
+                                            w.stride, w.scale)
+        assert G.o_excess(G.to_f64(o[b, h]), ref) <= 0, (b, h)
+        assert abs(float(lse[b, h]) - ref_lse) <= 1e-3, (b, h)
