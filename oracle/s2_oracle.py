@@ -14,6 +14,10 @@ What each function follows:
 * ``head_offset`` / ``block_mask`` - the per-head block mask M^h of the paper's
   section 4.2 (the unnumbered equation defining the "Local" and "Stride"
   cases), evaluated independently for every (h, i, j).
+* ``with_sink`` / ``homogeneous_mask`` / ``valid_custom_mask`` - the other
+  patterns of section 5.1's comparison (attention sink, same shards for all
+  heads) and the conditions any custom per-head pattern (section 3's
+  customisation claim) must meet.
 * ``compressed_layout`` - the compressed-sparse-row storage of that mask that
   section 3.2 ("Warmup") mentions, produced by scanning the dense mask.
 * ``token_mask`` - sharding of N tokens into ceil(N/S) blocks (section 3.2)
@@ -101,6 +105,34 @@ def block_mask(num_heads, num_blocks, local_blocks, stride, head_index_base=0,
         else:
             M[h] = local
     return M
+
+
+def with_sink(M, sink_blocks):
+    """The mask with the first `sink_blocks` KV blocks added to every row (the "+ Sink" variants
+    of section 5.1's table): M'[h][i][j] = M[h][i][j] or (j < sink_blocks and j <= i)."""
+    H, B, _ = M.shape
+    out = M.copy()
+    for i in range(B):
+        for j in range(min(int(sink_blocks), i + 1)):
+            out[:, i, j] = True
+    return out
+
+
+def homogeneous_mask(num_heads, num_blocks, local_blocks, stride, offset=0, window_blocks=0):
+    """Section 5.1's "Homogeneous" group: every head attends the same shards, i.e. the mask of
+    section 4.2 with one and the same offset for all heads."""
+    one = block_mask(1, num_blocks, local_blocks, stride, head_index_base=offset,
+                     window_blocks=window_blocks)
+    return np.repeat(one, int(num_heads), axis=0)
+
+
+def valid_custom_mask(M):
+    """What a caller-supplied block mask must satisfy for decoder attention: nothing above the
+    diagonal (causal), and the diagonal block kept in every row (a token attends itself, so no
+    softmax is empty)."""
+    H, B, _ = M.shape
+    i = np.arange(B)
+    return bool(not np.triu(M, k=1).any() and M[:, i, i].all())
 
 
 def compressed_layout(M):
