@@ -141,6 +141,18 @@ typedef struct {
  * caller until s2_layout_destroy.  Errors: NULL, BAD_PARAM (H<1, B<1, S not 64/128, B_l<1,
  * stride<0, window<0, head_index_base<0), OVERFLOW, HIP. */
 int s2_layout_build(const s2_layout_params* params, s2_layout** out);
+/* A layout from the caller's own per-head pattern instead of the section 4.2 rule (section 3
+ * promises patterns customised per head and per context range; section 5.1 compares several:
+ * attention sink, the same shards for all heads, plain sliding window).  row_ptr[H*B + 1] and
+ * col_idx[row_ptr[H*B]] are HOST int32 arrays in the order s2_layout_get returns them: rows
+ * ordered head-major, and inside a row the kept KV block columns strictly ascending, none above
+ * the row's own index (causal) and the row's own index last (a token always attends its own
+ * block, so no softmax is empty).  The arrays are copied.  The result works with s2_attn_fwd /
+ * s2_attn_bwd; decode takes its pattern from s2_layout_params and has no such variant.
+ * Errors: NULL, BAD_PARAM (H<1, B<1, S not 64/128, or a row breaking the rules above), OVERFLOW,
+ * HIP. */
+int s2_layout_from_csr(int32_t num_heads, int32_t num_blocks, int32_t block_size,
+                       const int32_t* row_ptr, const int32_t* col_idx, s2_layout** out);
 int s2_layout_destroy(s2_layout* layout);
 int s2_layout_get(const s2_layout* layout, s2_layout_view* out);
 

@@ -73,7 +73,7 @@ class PagedDecodeArgs(C.Structure):
 
 
 EXPORTS = (
-    "s2_layout_build", "s2_layout_destroy", "s2_layout_get", "s2_attn_fwd", "s2_attn_bwd",
+    "s2_layout_build", "s2_layout_from_csr", "s2_layout_destroy", "s2_layout_get", "s2_attn_fwd", "s2_attn_bwd",
     "s2_attn_bwd_workspace_bytes", "s2_attn_bwd_stages", "s2_dense_causal_fwd", "s2_dense_causal_bwd", "s2_attn_decode",
     "s2_attn_decode_workspace_bytes", "s2_attn_decode_default_splits", "s2_attn_decode_paged",
     "s2_kv_resident_blocks", "s2_status_string",
@@ -92,6 +92,8 @@ def lib():
         raise ImportError("libs2attn.so is not built: run `python -m paper_2407_17678_amd.build`")
     L = C.CDLL(LIB_PATH)
     L.s2_layout_build.argtypes = [C.POINTER(LayoutParams), C.POINTER(C.c_void_p)]
+    L.s2_layout_from_csr.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32),
+                                     C.POINTER(C.c_int32), C.POINTER(C.c_void_p)]
     L.s2_layout_destroy.argtypes = [C.c_void_p]
     L.s2_layout_get.argtypes = [C.c_void_p, C.POINTER(LayoutView)]
     L.s2_attn_fwd.argtypes = [C.c_void_p, C.POINTER(Tensors), C.c_float, C.c_void_p]
@@ -158,6 +160,19 @@ def s2_layout_build(params):
     out = C.c_void_p()
     _check(lib().s2_layout_build(C.byref(params), C.byref(out)), "s2_layout_build")
     return Layout(out, params)
+
+
+def s2_layout_from_csr(num_heads, num_blocks, block_size, row_ptr, col_idx):
+    """row_ptr, col_idx: host int32 arrays (numpy) in the order s2_layout_get returns them."""
+    import numpy as np
+    rp = np.ascontiguousarray(row_ptr, dtype=np.int32)
+    ci = np.ascontiguousarray(col_idx, dtype=np.int32)
+    assert rp.shape == (num_heads * num_blocks + 1,) and ci.shape == (int(rp[-1]),)
+    out = C.c_void_p()
+    as_p = lambda a: a.ctypes.data_as(C.POINTER(C.c_int32))
+    _check(lib().s2_layout_from_csr(num_heads, num_blocks, block_size, as_p(rp), as_p(ci), C.byref(out)),
+           "s2_layout_from_csr")
+    return Layout(out, None)
 
 
 def s2_layout_destroy(layout):

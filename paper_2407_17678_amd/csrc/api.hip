@@ -116,21 +116,19 @@ int check_layout_fits(const s2_layout* L, const s2_tensors* t) {
 
 extern "C" {
 
-int s2_layout_build(const s2_layout_params* params, s2_layout** out) {
-  if (!params || !out) return S2_ERR_NULL;
-  *out = nullptr;
-  s2_layout* L = new (std::nothrow) s2_layout();
-  if (!L) return S2_ERR_OVERFLOW;
-  int st;
-  try {
-    st = s2::build_host(*params, *L);
-    if (st == S2_OK) {
-      s2::build_tiles(*L, s2::kFwdBM / params->block_size, false, L->fwd_tiles);
-      s2::build_tiles(*L, s2::kBwdBM / params->block_size, false, L->q_tiles);
-      s2::build_tiles(*L, s2::kBwdBN / params->block_size, true, L->kv_tiles);
+namespace {
+// Tile lists for the three passes, then the device copy when a GPU is visible.  Takes ownership
+// of L: on failure it is deleted.
+int finish_layout(s2_layout* L, int st, s2_layout** out) {
+  if (st == S2_OK) {
+    try {
+      const int S = L->p.block_size;
+      s2::build_tiles(*L, s2::kFwdBM / S, false, L->fwd_tiles);
+      s2::build_tiles(*L, s2::kBwdBM / S, false, L->q_tiles);
+      s2::build_tiles(*L, s2::kBwdBN / S, true, L->kv_tiles);
+    } catch (const std::bad_alloc&) {
+      st = S2_ERR_OVERFLOW;
     }
-  } catch (const std::bad_alloc&) {
-    st = S2_ERR_OVERFLOW;
   }
   if (st != S2_OK) {
     delete L;
@@ -155,6 +153,36 @@ int s2_layout_build(const s2_layout_params* params, s2_layout** out) {
   }
   *out = L;
   return S2_OK;
+}
+}  // namespace
+
+int s2_layout_build(const s2_layout_params* params, s2_layout** out) {
+  if (!params || !out) return S2_ERR_NULL;
+  *out = nullptr;
+  s2_layout* L = new (std::nothrow) s2_layout();
+  if (!L) return S2_ERR_OVERFLOW;
+  int st;
+  try {
+    st = s2::build_host(*params, *L);
+  } catch (const std::bad_alloc&) {
+    st = S2_ERR_OVERFLOW;
+  }
+  return finish_layout(L, st, out);
+}
+
+int s2_layout_from_csr(int32_t num_heads, int32_t num_blocks, int32_t block_size, const int32_t* row_ptr,
+                       const int32_t* col_idx, s2_layout** out) {
+  if (!row_ptr || !col_idx || !out) return S2_ERR_NULL;
+  *out = nullptr;
+  s2_layout* L = new (std::nothrow) s2_layout();
+  if (!L) return S2_ERR_OVERFLOW;
+  int st;
+  try {
+    st = s2::build_from_csr(num_heads, num_blocks, block_size, row_ptr, col_idx, *L);
+  } catch (const std::bad_alloc&) {
+    st = S2_ERR_OVERFLOW;
+  }
+  return finish_layout(L, st, out);
 }
 
 int s2_layout_destroy(s2_layout* layout) {

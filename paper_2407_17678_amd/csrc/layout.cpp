@@ -55,6 +55,25 @@ inline void for_col(const s2_layout_params& p, int o, int j, F&& emit) {
 
 }  // namespace
 
+namespace {
+// union over heads covers every causal block?
+int covers_all_blocks(const s2_layout& L) {
+  const int H = L.p.num_heads, B = L.p.num_blocks;
+  std::vector<uint8_t> seen((size_t)B);
+  for (int i = 0; i < B; ++i) {
+    std::fill(seen.begin(), seen.begin() + i + 1, 0);
+    for (int h = 0; h < H; ++h) {
+      const int32_t* c = L.col_idx.data() + L.row_ptr[(size_t)h * B + i];
+      const int32_t* e = L.col_idx.data() + L.row_ptr[(size_t)h * B + i + 1];
+      for (; c != e; ++c) seen[*c] = 1;
+    }
+    for (int j = 0; j <= i; ++j)
+      if (!seen[j]) return 0;
+  }
+  return 1;
+}
+}  // namespace
+
 int64_t row_blocks(const s2_layout_params& p, int head, int i, int32_t* out, int64_t capacity) {
   int64_t n = 0;
   for_row(p, head_offset(p, head), i, [&](int j) {
@@ -113,22 +132,57 @@ int build_host(const s2_layout_params& p, s2_layout& L) {
   }
   if (n != nnz) return S2_ERR_BAD_PARAM;  // the two closed forms disagree: a bug, never silent
 
-  // union over heads covers every causal block?  Count distinct (i,j) kept by any head.
-  {
-    std::vector<uint8_t> seen((size_t)B);
-    bool all = true;
-    for (int i = 0; i < B && all; ++i) {
-      std::fill(seen.begin(), seen.begin() + i + 1, 0);
-      for (int h = 0; h < H; ++h) {
-        const int32_t* c = L.col_idx.data() + L.row_ptr[(size_t)h * B + i];
-        const int32_t* e = L.col_idx.data() + L.row_ptr[(size_t)h * B + i + 1];
-        for (; c != e; ++c) seen[*c] = 1;
-      }
-      for (int j = 0; j <= i; ++j)
-        if (!seen[j]) { all = false; break; }
+  L.covers_all = covers_all_blocks(L);
+  return S2_OK;
+}
+
+int build_from_csr(int num_heads, int num_blocks, int block_size, const int32_t* row_ptr,
+                   const int32_t* col_idx, s2_layout& L) {
+  if (num_heads < 1 || num_blocks < 1) return S2_ERR_BAD_PARAM;
+  if (block_size != 64 && block_size != 128) return S2_ERR_BAD_PARAM;
+  const int H = num_heads, B = num_blocks;
+  if ((int64_t)H * B + 1 > std::numeric_limits<int32_t>::max()) return S2_ERR_OVERFLOW;
+  if ((int64_t)B * block_size > std::numeric_limits<int32_t>::max()) return S2_ERR_OVERFLOW;
+  const size_t rows = (size_t)H * B;
+  if (row_ptr[0] != 0) return S2_ERR_BAD_PARAM;
+  int max_row = 0;
+  for (size_t r = 0; r < rows; ++r) {
+    const int64_t lo = row_ptr[r], hi = row_ptr[r + 1];
+    if (hi <= lo) return S2_ERR_BAD_PARAM;  // every row keeps at least its diagonal block
+    const int i = (int)(r % B);
+    // strictly ascending, none above the diagonal, the diagonal itself last
+    for (int64_t n = lo; n < hi; ++n) {
+      const int j = col_idx[n];
+      if (j < 0 || j > i) return S2_ERR_BAD_PARAM;
+      if (n > lo && j <= col_idx[n - 1]) return S2_ERR_BAD_PARAM;
     }
-    L.covers_all = all ? 1 : 0;
+    if (col_idx[hi - 1] != i) return S2_ERR_BAD_PARAM;
+    max_row = std::max(max_row, (int)(hi - lo));
   }
+  const int64_t nnz = row_ptr[rows];
+  L.p = s2_layout_params{};
+  L.p.num_heads = H;
+  L.p.num_blocks = B;
+  L.p.block_size = block_size;
+  L.nnz = nnz;
+  L.max_row_blocks = max_row;
+  L.row_ptr.assign(row_ptr, row_ptr + rows + 1);
+  L.col_idx.assign(col_idx, col_idx + nnz);
+  // transpose by counting; rows come out ascending inside each column because rows are visited
+  // in ascending order
+  L.col_ptr.assign(rows + 1, 0);
+  for (int h = 0; h < H; ++h)
+    for (int i = 0; i < B; ++i)
+      for (int32_t n = row_ptr[(size_t)h * B + i]; n < row_ptr[(size_t)h * B + i + 1]; ++n)
+        ++L.col_ptr[(size_t)h * B + col_idx[n] + 1];
+  for (size_t r = 0; r < rows; ++r) L.col_ptr[r + 1] += L.col_ptr[r];
+  L.row_idx.resize((size_t)nnz);
+  std::vector<int32_t> fill(L.col_ptr.begin(), L.col_ptr.end() - 1);
+  for (int h = 0; h < H; ++h)
+    for (int i = 0; i < B; ++i)
+      for (int32_t n = row_ptr[(size_t)h * B + i]; n < row_ptr[(size_t)h * B + i + 1]; ++n)
+        L.row_idx[(size_t)fill[(size_t)h * B + col_idx[n]]++] = i;
+  L.covers_all = covers_all_blocks(L);
   return S2_OK;
 }
 

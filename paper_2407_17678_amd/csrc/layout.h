@@ -47,6 +47,9 @@ struct s2_layout {
 namespace s2 {
 // Host-only construction (no HIP calls).  Returns an S2_* status.
 int build_host(const s2_layout_params& p, s2_layout& L);
+// The same from caller-supplied compressed rows (validated: ascending, causal, diagonal kept).
+int build_from_csr(int num_heads, int num_blocks, int block_size, const int32_t* row_ptr,
+                   const int32_t* col_idx, s2_layout& L);
 // Kept block columns of block row i of local head `head`, ascending, in closed form (no layout
 // needed, any i >= 0): writes at most `capacity` of them to out and returns how many there are.
 int64_t row_blocks(const s2_layout_params& p, int head, int i, int32_t* out, int64_t capacity);

@@ -238,3 +238,56 @@ def test_paged_decode_argument_errors_without_launch():
     assert lib.s2_attn_decode_paged(C.byref(p), C.byref(a), 1.0, None, 0, None) == -2
     a.num_splits = 0
     assert lib.s2_attn_decode_paged(C.byref(p), C.byref(a), 1.0, None, 0, None) == -5   # workspace
+
+
+def _random_causal_mask(rng, H, Bk, density):
+    M = np.tril(rng.random((H, Bk, Bk)) < density)
+    i = np.arange(Bk)
+    M[:, i, i] = True
+    return M
+
+
+def test_layout_from_csr_round_trip_and_transpose():
+    # caller-supplied patterns: the library must hand back the same rows and the exact transpose
+    rng = np.random.default_rng(21)
+    masks = [orc.with_sink(orc.block_mask(4, 24, 3, 4), 2),
+             orc.homogeneous_mask(3, 17, 2, 5, offset=3),
+             orc.block_mask(2, 9, 4, 0)]
+    masks += [_random_causal_mask(rng, int(rng.integers(1, 6)), int(rng.integers(1, 40)), float(rng.random()))
+              for _ in range(40)]
+    for M in masks:
+        H, Bk, _ = M.shape
+        assert orc.valid_custom_mask(M)
+        row_ptr, col_idx, col_ptr, row_idx = orc.compressed_layout(M)
+        for S in (64, 128):
+            lay = B.s2_layout_from_csr(H, Bk, S, row_ptr, col_idx)
+            got = B.s2_layout_get(lay)
+            assert got["nnz"] == int(M.sum()) and got["block_size"] == S
+            for name, want in (("row_ptr", row_ptr), ("col_idx", col_idx), ("col_ptr", col_ptr),
+                               ("row_idx", row_idx)):
+                assert np.array_equal(got[name], want), name
+            assert got["covers_all"] == int(orc.covers_all(M))
+            assert got["max_row_blocks"] == int(M.sum(axis=2).max())
+            B.s2_layout_destroy(lay)
+
+
+def test_layout_from_csr_rejects_bad_rows():
+    lib = B.lib()
+    out = C.c_void_p()
+    arr = lambda xs: (C.c_int32 * len(xs))(*xs)
+    call = lambda H, Bk, S, rp, ci: lib.s2_layout_from_csr(H, Bk, S, arr(rp), arr(ci), C.byref(out))
+    good_rp, good_ci = [0, 1, 3, 5], [0, 0, 1, 0, 2]      # 1 head, 3 blocks
+    assert call(1, 3, 64, good_rp, good_ci) == 0
+    lib.s2_layout_destroy(out)
+    assert lib.s2_layout_from_csr(1, 3, 64, None, arr(good_ci), C.byref(out)) == -1
+    assert lib.s2_layout_from_csr(1, 3, 64, arr(good_rp), None, C.byref(out)) == -1
+    assert lib.s2_layout_from_csr(1, 3, 64, arr(good_rp), arr(good_ci), None) == -1
+    assert call(0, 3, 64, good_rp, good_ci) == -2
+    assert call(1, 0, 64, good_rp, good_ci) == -2
+    assert call(1, 3, 32, good_rp, good_ci) == -2
+    assert call(1, 3, 64, [1, 2, 4, 6], good_ci + [0]) == -2        # row_ptr[0] != 0
+    assert call(1, 3, 64, [0, 1, 1, 3], [0, 0, 2]) == -2            # empty row
+    assert call(1, 3, 64, [0, 1, 3, 5], [0, 1, 1, 0, 2]) == -2      # not strictly ascending
+    assert call(1, 3, 64, [0, 1, 3, 5], [0, 0, 2, 0, 2]) == -2      # above the diagonal
+    assert call(1, 3, 64, [0, 1, 3, 4], [0, 0, 1, 1]) == -2         # diagonal missing in row 2
+    assert call(1, 3, 64, [0, 1, 3, 5], [0, 0, 1, -1, 2]) == -2     # negative column
