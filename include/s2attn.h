@@ -164,6 +164,16 @@ int s2_layout_get(const s2_layout* layout, s2_layout_view* out);
  * BAD_PARAM (scale), NO_DEVICE, HIP. */
 int s2_attn_fwd(const s2_layout* layout, const s2_tensors* t, float scale, void* stream);
 
+/* The same for a run of query rows only (chunked prefill when serving, section 5.3's prefill
+ * measurements): t->q, t->o and t->lse hold q_rows rows, row r being the token at sequence
+ * position q_row_start + r; t->k and t->v hold t->seqlen rows from position 0, with
+ * q_row_start + q_rows <= t->seqlen <= B*S of the layout (keys after a query are never read).
+ * q_row_start and q_rows must be multiples of 128, q_rows >= 128.  lse is [batch, heads, q_rows].
+ * Every row comes out bit-identical to the same row of s2_attn_fwd on the whole sequence.
+ * Errors as s2_attn_fwd. */
+int s2_attn_fwd_rows(const s2_layout* layout, const s2_tensors* t, int32_t q_row_start,
+                     int32_t q_rows, float scale, void* stream);
+
 /* ---- backward (gradient of the above) ---------------------------------------------------- */
 
 /* Given q,k,v,o,lse,d_o writes dq,dk,dv (bf16; fp32 accumulation).  workspace is DEVICE memory

@@ -300,8 +300,10 @@ def forward_rows(q_rows, row_index, k, v, Mh, block_size, scale):
     """Forward for selected query rows of one head (rows are independent).
 
     q_rows [R,D] are the queries at absolute positions ``row_index`` [R];
-    k, v hold all N keys.  Used to sample outputs at sizes where the full
-    score matrix is too large.
+    k, v hold the keys from position 0 up to at least the last of those
+    positions.  This is also the definition of a prefill chunk (a run of query
+    rows against the keys cached so far), and it is used to sample outputs at
+    sizes where the full score matrix is too large.
     """
     q_rows, k, v = _f64(q_rows), _f64(k), _f64(v)
     N = k.shape[0]

@@ -73,7 +73,7 @@ class PagedDecodeArgs(C.Structure):
 
 
 EXPORTS = (
-    "s2_layout_build", "s2_layout_from_csr", "s2_layout_destroy", "s2_layout_get", "s2_attn_fwd", "s2_attn_bwd",
+    "s2_layout_build", "s2_layout_from_csr", "s2_layout_destroy", "s2_layout_get", "s2_attn_fwd", "s2_attn_fwd_rows", "s2_attn_bwd",
     "s2_attn_bwd_workspace_bytes", "s2_attn_bwd_stages", "s2_dense_causal_fwd", "s2_dense_causal_bwd", "s2_attn_decode",
     "s2_attn_decode_workspace_bytes", "s2_attn_decode_default_splits", "s2_attn_decode_paged",
     "s2_kv_resident_blocks", "s2_status_string",
@@ -97,6 +97,7 @@ def lib():
     L.s2_layout_destroy.argtypes = [C.c_void_p]
     L.s2_layout_get.argtypes = [C.c_void_p, C.POINTER(LayoutView)]
     L.s2_attn_fwd.argtypes = [C.c_void_p, C.POINTER(Tensors), C.c_float, C.c_void_p]
+    L.s2_attn_fwd_rows.argtypes = [C.c_void_p, C.POINTER(Tensors), C.c_int32, C.c_int32, C.c_float, C.c_void_p]
     L.s2_attn_bwd.argtypes = [C.c_void_p, C.POINTER(Tensors), C.c_float, C.c_void_p, C.c_size_t, C.c_void_p]
     L.s2_attn_bwd_stages.argtypes = [C.c_void_p, C.POINTER(Tensors), C.c_float, C.c_void_p, C.c_size_t,
                                      C.c_int, C.c_void_p]
@@ -221,6 +222,14 @@ def _tensors(q, k, v, o, lse, d_o=None, dq=None, dk=None, dv=None):
 def s2_attn_fwd(layout, q, k, v, o, lse, scale, stream=None):
     t = _tensors(q, k, v, o, lse)
     _check(lib().s2_attn_fwd(layout.handle, C.byref(t), scale, _stream_ptr(stream)), "s2_attn_fwd")
+
+
+def s2_attn_fwd_rows(layout, q, k, v, o, lse, q_row_start, scale, stream=None):
+    """q, o: [Bt, H, q_rows, D] (the tokens at positions q_row_start ...); k, v: [Bt, H, N_k, D]."""
+    t = _tensors(q, k, v, o, lse)
+    t.seqlen = k.shape[2]
+    _check(lib().s2_attn_fwd_rows(layout.handle, C.byref(t), q_row_start, q.shape[2], scale,
+                                  _stream_ptr(stream)), "s2_attn_fwd_rows")
 
 
 def s2_attn_bwd_workspace_bytes(batch, heads, seqlen, head_dim):

@@ -93,6 +93,8 @@ s2::AttnParams make_params(const s2_tensors* t, float scale) {
   p.batch = t->batch;
   p.heads = t->heads;
   p.seqlen = t->seqlen;
+  p.q_row0 = 0;
+  p.q_rows = t->seqlen;
   p.head_dim = t->head_dim;
   p.q_sb = t->q_stride_b;
   p.q_sh = t->q_stride_h;
@@ -238,6 +240,27 @@ size_t s2_attn_bwd_workspace_bytes(int32_t batch, int32_t heads, int32_t seqlen,
 int s2_attn_bwd(const s2_layout* layout, const s2_tensors* t, float scale, void* workspace,
                 size_t workspace_bytes, void* stream) {
   return s2_attn_bwd_stages(layout, t, scale, workspace, workspace_bytes, S2_BWD_ALL, stream);
+}
+
+int s2_attn_fwd_rows(const s2_layout* layout, const s2_tensors* t, int32_t q_row_start, int32_t q_rows,
+                     float scale, void* stream) {
+  if (!layout) return S2_ERR_NULL;
+  int st = check_tensors(t, false, scale);
+  if (st != S2_OK) return st;
+  if (t->heads != layout->p.num_heads) return S2_ERR_SHAPE;
+  if ((int64_t)t->seqlen > (int64_t)layout->p.num_blocks * layout->p.block_size) return S2_ERR_SHAPE;
+  if (q_row_start < 0 || q_rows < s2::kFwdBM || q_row_start % s2::kFwdBM != 0 || q_rows % s2::kFwdBM != 0)
+    return S2_ERR_SHAPE;
+  if ((int64_t)q_row_start + q_rows > t->seqlen) return S2_ERR_SHAPE;
+  if (!layout->on_device) return S2_ERR_NO_DEVICE;
+  s2::AttnParams p = make_params(t, scale);
+  p.q_row0 = q_row_start;
+  p.q_rows = q_rows;
+  p.block_size = layout->p.block_size;
+  p.fwd_tiles = dev_tiles(layout->fwd_tiles);
+  p.q_tiles = dev_tiles(layout->q_tiles);
+  p.kv_tiles = dev_tiles(layout->kv_tiles);
+  return hip_ok(s2::launch_fwd(p, false, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
 }
 
 int s2_attn_bwd_stages(const s2_layout* layout, const s2_tensors* t, float scale, void* workspace,

@@ -41,18 +41,22 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63, l32 = lane & 31, half = lane >> 5;
-  const int T = p.fwd_tiles.tiles_per_head;
+  const int T = p.fwd_tiles.tiles_per_head;      // tiles of the whole sequence (indexes the lists)
+  const int T_run = (p.q_rows + BM - 1) / BM;    // tiles this launch computes
   int bh, rank;
-  if (!map_workgroup(blockIdx.x, p.batch * p.heads, T, bh, rank)) return;
+  if (!map_workgroup(blockIdx.x, p.batch * p.heads, T_run, bh, rank)) return;
   const int b = bh / p.heads, h = bh - b * p.heads;
-  const int tile = DENSE ? (T - 1 - rank) : p.fwd_tiles.order[h * T + rank];
+  // longest tiles first: by the layout's order for a whole sequence, else simply last row first
+  const bool whole = p.q_row0 == 0 && T_run == T;
+  const int tile = (DENSE || !whole) ? p.q_row0 / BM + (T_run - 1 - rank) : p.fwd_tiles.order[h * T + rank];
   const int S = DENSE ? kChunk : p.block_size;
   const int cpb = S / CH;  // steps per mask block: a power of two, so / and % below are a shift and a mask
   const int cpb_sh = __builtin_ctz(cpb), cpb_m = cpb - 1;
 
   const int N = p.seqlen;
-  const int qw0 = tile * BM + wave * MW;  // first query row of this wavefront
-  const bool wave_active = qw0 < N;
+  const int qw0 = tile * BM + wave * MW;  // first query row of this wavefront (sequence position)
+  const int ql0 = qw0 - p.q_row0;         // the same as a row of q / o / lse
+  const bool wave_active = ql0 < p.q_rows;
   const int my_member = (qw0 / S) - tile * (BM / S);  // which mask row of the tile I am in
 
   const uint16_t* qb = p.q + b * p.q_sb + h * p.q_sh;
@@ -64,7 +68,7 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
 #pragma unroll
   for (int kk = 0; kk < D / 16; ++kk) {
     if (wave_active)
-      qf[kk] = *reinterpret_cast<const bf16x8*>(qb + (int64_t)(qw0 + l32) * p.q_st + 16 * kk + 8 * half);
+      qf[kk] = *reinterpret_cast<const bf16x8*>(qb + (int64_t)(ql0 + l32) * p.q_st + 16 * kk + 8 * half);
     else
       qf[kk] = bf16x8{};
   }
@@ -220,7 +224,7 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
   if (!wave_active) return;
   const float l_tot = sum_halves(l_run);
   const float inv = 1.0f / l_tot;
-  const int qrow = qw0 + l32;
+  const int qrow = ql0 + l32;
   uint16_t* orow = p.o + b * p.q_sb + h * p.q_sh + (int64_t)qrow * p.q_st;
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt)
@@ -231,13 +235,12 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
       for (int e = 0; e < 4; ++e) w[e] = (__bf16)(acc_o[dt][4 * g + e] * inv);
       *reinterpret_cast<bf16x4*>(orow + 32 * dt + 8 * g + 4 * half) = w;
     }
-  if (half == 0) p.lse[((int64_t)b * p.heads + h) * N + qrow] = m_run * p.scale + __logf(l_tot);
+  if (half == 0) p.lse[((int64_t)b * p.heads + h) * p.q_rows + qrow] = m_run * p.scale + __logf(l_tot);
 }
 
 template <int D, bool DENSE>
 hipError_t launch_one(const AttnParams& p, hipStream_t stream) {
-  const int T = p.fwd_tiles.tiles_per_head;
-  const int grid = grid_for(p.batch * p.heads, T);
+  const int grid = grid_for(p.batch * p.heads, (p.q_rows + kFwdBM - 1) / kFwdBM);
   hipLaunchKernelGGL((fwd_kernel<D, DENSE, kFwdChunk>), dim3(grid), dim3(kThreads), 0, stream, p);
   return hipGetLastError();
 }

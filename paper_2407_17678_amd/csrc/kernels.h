@@ -29,6 +29,9 @@ struct AttnParams {
   float* delta;  // workspace: rowsum(dO * O), [batch, heads, seqlen]
   float* lse2;   // workspace: lse * log2(e), [batch, heads, seqlen]
   int batch, heads, seqlen, head_dim;
+  // forward only: q, o, lse hold q_rows rows, local row r being sequence position q_row0 + r
+  // (the whole sequence: q_row0 = 0, q_rows = seqlen)
+  int q_row0, q_rows;
   int64_t q_sb, q_sh, q_st;
   int64_t kv_sb, kv_sh, kv_st;
   float scale;        // softmax scale

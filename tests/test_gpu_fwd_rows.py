@@ -1,0 +1,72 @@
+"""GPU parity of the forward over a run of query rows (chunked prefill) against the oracle's
+forward_rows, and bit-identity with the same rows of the whole-sequence forward."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import s2_oracle as orc
+from paper_2407_17678_amd import binding as B
+from paper_2407_17678_amd import synth
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("name,heads,seqlen,chunks", [
+    ("7b_32k", 3, 4096, [(0, 128), (128, 384), (1024, 1024), (3968, 128), (2048, 2048)]),
+    ("7b_128k", 2, 2048, [(0, 256), (512, 512), (1920, 128)]),     # S = 128
+    ("tiny", 4, 1024, [(0, 1024), (256, 128), (640, 384)]),        # D = 64
+])
+def test_forward_rows(name, heads, seqlen, chunks):
+    w = synth.WORKLOADS[name]
+    S = w.block_size
+    qb, kb, vb, _ = synth.train_inputs(w, heads=heads, batch=2, seqlen=seqlen)
+    q, k, v = G.to_dev(qb), G.to_dev(kb), G.to_dev(vb)
+    # a layout for a context twice as long as what is cached: the chunk API only needs B*S >= N_k
+    lay_long = B.s2_layout_build(B.layout_params(heads, 2 * seqlen // S, S, w.local_blocks, w.stride))
+    lay = B.s2_layout_build(B.layout_params(heads, seqlen // S, S, w.local_blocks, w.stride))
+    o_full = torch.empty_like(q)
+    lse_full = torch.empty((2, heads, seqlen), dtype=torch.float32, device="cuda")
+    B.s2_attn_fwd(lay, q, k, v, o_full, lse_full, w.scale)
+    torch.cuda.synchronize()
+    M = orc.block_mask(heads, 2 * seqlen // S, w.local_blocks, w.stride)
+    f = G.bits_f64
+    for (r0, n) in chunks:
+        print("forward rows case", name, "rows", r0, "+", n, flush=True)
+        n_k = r0 + n   # only the keys up to the chunk's end are handed over
+        qc = q[:, :, r0:r0 + n].contiguous()
+        kc, vc = k[:, :, :n_k].contiguous(), v[:, :, :n_k].contiguous()
+        oc = torch.empty_like(qc)
+        lc = torch.empty((2, heads, n), dtype=torch.float32, device="cuda")
+        B.s2_attn_fwd_rows(lay_long, qc, kc, vc, oc, lc, r0, w.scale)
+        torch.cuda.synchronize()
+        assert torch.equal(oc, o_full[:, :, r0:r0 + n]) and torch.equal(lc, lse_full[:, :, r0:r0 + n])
+        rows = np.arange(r0, r0 + n)
+        for b, h in ((0, 0), (1, heads - 1)):
+            O, LSE = orc.forward_rows(f(qb)[b, h, rows], rows, f(kb)[b, h, :n_k], f(vb)[b, h, :n_k], M[h], S, w.scale)
+            assert G.o_excess(G.to_f64(oc[b, h]), O) <= 0
+            assert np.abs(G.to_f64(lc[b, h]) - LSE).max() <= 1e-3
+
+
+def test_forward_rows_argument_errors():
+    w = synth.WORKLOADS["tiny"]
+    H, S = 2, w.block_size
+    lay = B.s2_layout_build(B.layout_params(H, 8, S, w.local_blocks, w.stride))
+    mk = lambda n: torch.zeros((1, H, n, 64), dtype=torch.bfloat16, device="cuda")
+    k = mk(512)
+    lse = torch.empty((1, H, 128), dtype=torch.float32, device="cuda")
+    def status(q, r0, kk=k, layout=lay):
+        try:
+            B.s2_attn_fwd_rows(layout, q, kk, kk, torch.empty_like(q), lse, r0, w.scale)
+        except B.S2Error as e:
+            return e.status
+        return 0
+    assert status(mk(128), 0) == 0
+    assert status(mk(128), 64) == -3          # start not a multiple of 128
+    assert status(mk(64), 0) == -3            # fewer than 128 rows
+    assert status(mk(192), 0) == -3           # not a multiple of 128
+    assert status(mk(128), 512) == -3         # runs past the keys
+    assert status(mk(128), -128) == -3
+    assert status(mk(128), 0, kk=mk(1024)) == -3   # more keys than the layout has blocks for
+    torch.cuda.synchronize()
