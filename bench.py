@@ -64,7 +64,7 @@ def measured_traffic(workload, kernel):
     return None
 
 
-def bench_train(w, steps, warmup, with_dense=True, with_bwd=True, dense_steps=3):
+def bench_train(w, steps, warmup, with_dense=True, with_bwd=True, dense_steps=3, hybrid_layers=None):
     """Times fwd(+bwd) of workload `w`; returns a dict of timings and derived rates."""
     import torch
     from paper_2407_17678_amd import binding as B
@@ -143,6 +143,26 @@ def bench_train(w, steps, warmup, with_dense=True, with_bwd=True, dense_steps=3)
         res["dense_tflops"] = dflops / (res["dense_ms_per_step"] * 1e-3) / 1e12
         res["speedup_vs_dense"] = res["dense_ms_per_step"] / ms_step
         res["speedup_vs_dense_fwd"] = res["dense_ms_fwd"] / res["ms_fwd"]
+        if hybrid_layers:
+            # Attention time of a whole layer stack that keeps a few layers dense (section 4.2's
+            # hybrid architecture: dense attention in about 1/6 of the layers): every layer's
+            # forward in order, then every layer's backward in reverse order, one launch set per
+            # layer as a model would issue them.
+            n_layers, n_dense = hybrid_layers
+            every = n_layers / n_dense
+            dense_at = {int(i * every) for i in range(n_dense)}
+
+            def stack(all_dense):
+                for l in range(n_layers):
+                    (dfwd if all_dense or l in dense_at else fwd)()
+                if with_bwd:
+                    for l in reversed(range(n_layers)):
+                        (dbwd if all_dense or l in dense_at else bwd)()
+            ms_h = time_events(lambda: stack(False), 2, 1)
+            ms_d = time_events(lambda: stack(True), 1, 0)
+            frac = (n_dense * dense_pairs + (n_layers - n_dense) * pairs) / (n_layers * dense_pairs)
+            res["hybrid_stack"] = dict(layers=n_layers, dense_layers=sorted(dense_at), ms=ms_h, all_dense_ms=ms_d,
+                                       speedup=ms_d / ms_h, flop_fraction_of_dense=frac)
         step()  # leave the sparse path's outputs in place for the parity sample
 
     # roofline of the dominant kernel.  Flops attributed per kernel (sums to 14*D*pairs):
@@ -314,6 +334,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--extra", action="store_true", help="also time the other workloads (reported under 'extra')")
+    ap.add_argument("--hybrid-stack", default=None, metavar="LAYERS:DENSE",
+                    help="also time the attention of a LAYERS-layer stack with DENSE of them dense, e.g. 32:5")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a 1 GiB device-to-device copy, so that a rocprofv3 --pmc run has a kernel "
                          "of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -355,8 +377,9 @@ def main():
         return
 
     with_bwd = w.name != "7b_128k"
+    hybrid = tuple(int(x) for x in args.hybrid_stack.split(":")) if args.hybrid_stack else None
     res, tensors = bench_train(w, args.steps, args.warmup, with_dense=not args.no_dense, with_bwd=with_bwd,
-                               dense_steps=2 if w.seqlen > 40000 else 3)
+                               dense_steps=2 if w.seqlen > 40000 else 3, hybrid_layers=hybrid)
     roof = res.pop("roofline")
     cpu, parity = None, None
     if not args.no_cpu_baseline:
