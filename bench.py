@@ -342,7 +342,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; --gpus %d is not supported (heads and batch "
-                 "shard without communication, see DESIGN.md)" % args.gpus)
+                 "shard across GPUs without communication)" % args.gpus)
     if int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: launched with WORLD_SIZE > 1; this build runs on one GPU")
 

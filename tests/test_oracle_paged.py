@@ -75,7 +75,7 @@ def test_resident_set_is_the_current_row_when_the_window_is_unbounded(seed):
 
 def test_resident_count_closed_form_and_memory_ratio():
     # local blocks + stripes at or before i - B_l; at the 7B decode shape a head keeps about 1/9
-    # of a 32K cache (section 4.1's point; the survey's 9.3x byte ratio at those lengths)
+    # of a 32K cache (section 4.1's point)
     for g in (0, 5, 15, 31):
         for L in (8192, 20000, 32768):
             i = (L - 1) // 64
