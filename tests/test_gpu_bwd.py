@@ -68,3 +68,35 @@ def test_backward_is_bitwise_repeatable():
     b = G.run_fwd_bwd(w, qb, kb, vb, gb)
     for n in ("o", "lse", "dq", "dk", "dv"):
         assert torch.equal(a[n], b[n]), n
+
+
+def test_strided_tensors_backward():
+    """[Bt, N, H, D] storage viewed as [Bt, H, N, D] for every tensor, gradients included; K/V with a
+    padded token stride (a cache row longer than head_dim)."""
+    from paper_2407_17678_amd import binding as B
+    w = synth.WORKLOADS["1p3b_8k"]
+    H, Bt, N, D = 3, 2, 768, w.head_dim
+    qb, kb, vb, gb = synth.train_inputs(w, heads=H, batch=Bt, seqlen=N)
+    bnhd = lambda bits: G.to_dev(np.ascontiguousarray(bits.transpose(0, 2, 1, 3))).permute(0, 2, 1, 3)
+    q, g = bnhd(qb), bnhd(gb)
+    # K and V: rows of 2*D elements of which the first D are used
+    def padded(bits):
+        t = torch.zeros((Bt, H, N, 2 * D), dtype=torch.bfloat16, device="cuda")
+        t[..., :D] = G.to_dev(bits)
+        return t[..., :D]
+    k, v = padded(kb), padded(vb)
+    like_q = lambda: torch.empty_like(q.permute(0, 2, 1, 3)).permute(0, 2, 1, 3)
+    like_k = lambda: torch.zeros((Bt, H, N, 2 * D), dtype=torch.bfloat16, device="cuda")[..., :D]
+    o, dq, dk, dv = like_q(), like_q(), like_k(), like_k()
+    lse = torch.empty((Bt, H, N), dtype=torch.float32, device="cuda")
+    ws = torch.empty(B.s2_attn_bwd_workspace_bytes(Bt, H, N, D), dtype=torch.uint8, device="cuda")
+    lay = B.s2_layout_build(B.layout_params(H, N // w.block_size, w.block_size, w.local_blocks, w.stride))
+    B.s2_attn_fwd(lay, q, k, v, o, lse, w.scale)
+    B.s2_attn_bwd(lay, q, k, v, o, lse, g, dq, dk, dv, w.scale, ws)
+    torch.cuda.synchronize()
+    M = G.oracle_mask(w, H, N)
+    dQ, dK, dV, O, LSE = orc.attention_backward(G.bits_f64(qb), G.bits_f64(kb), G.bits_f64(vb),
+                                                G.bits_f64(gb), M, w.block_size, w.scale)
+    assert G.o_excess(G.to_f64(o), O) <= 0
+    for n, got, ref in (("dq", dq, dQ), ("dk", dk, dK), ("dv", dv, dV)):
+        assert G.rel_l2(G.to_f64(got), ref) <= GRAD_TOL, n
