@@ -59,16 +59,19 @@ __global__ __launch_bounds__(256) void delta_kernel(const AttnParams p) {
 
 // ------------------------------------------------------------------------------------ dq
 
-template <int D>
+// CH = keys per step: 64, or 32 for 32-token mask blocks.
+template <int D, int CH>
 struct DqSmem {
-  uint16_t k[2][DmaTile<D>::kElems];
-  uint16_t v[2][DmaTile<D>::kElems];
+  uint16_t k[2][DmaTile<D, CH>::kElems];
+  uint16_t v[2][DmaTile<D, CH>::kElems];
 };
 
-template <int D, bool DENSE>
+template <int D, bool DENSE, int CH>
 __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
+  typedef DmaTile<D, CH> Tile;
+  constexpr int KT = CH / 32;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  DqSmem<D>& sm = *reinterpret_cast<DqSmem<D>*>(smem_raw);
+  DqSmem<D, CH>& sm = *reinterpret_cast<DqSmem<D, CH>*>(smem_raw);
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -79,7 +82,7 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
   const int b = bh / p.heads, h = bh - b * p.heads;
   const int tile = DENSE ? (T - 1 - rank) : p.q_tiles.order[h * T + rank];
   const int S = DENSE ? kChunk : p.block_size;
-  const int cpb = S / kChunk;  // a power of two: / and % below are a shift and a mask
+  const int cpb = S / CH;  // a power of two: / and % below are a shift and a mask
   const int cpb_sh = __builtin_ctz(cpb), cpb_m = cpb - 1;
   const int N = p.seqlen;
   const int qw0 = tile * kBwdBM + wave * 32;
@@ -93,7 +96,7 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
 
   int ent_lo = 0, n_ent;
   if (DENSE) {
-    n_ent = min(N, (tile + 1) * kBwdBM) / kChunk;
+    n_ent = min(N, (tile + 1) * kBwdBM) / kChunk;  // dense blocks are kChunk keys
   } else {
     ent_lo = p.q_tiles.ptr[h * T + tile];
     n_ent = p.q_tiles.ptr[h * T + tile + 1] - ent_lo;
@@ -104,32 +107,32 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
   // chunk `it` of the tile's list: its first row, and whether my mask row / column keeps it
   auto chunk_of = [&](int it, int& kv0, bool& keep) {
     if (DENSE) {
-      kv0 = it * kChunk;
+      kv0 = it * CH;
       keep = true;
     } else {
       const int e = list.get((it >> cpb_sh), lane);
-      kv0 = (e >> 8) * S + ((it & cpb_m)) * kChunk;
+      kv0 = (e >> 8) * S + ((it & cpb_m)) * CH;
       keep = (e >> my_member) & 1;
     }
   };
   // first row of chunk it+1, right after chunk_of(it)
   auto next_chunk_of = [&](int it, int& kv0_n) {
     if (DENSE) {
-      kv0_n = (it + 1) * kChunk;
+      kv0_n = (it + 1) * CH;
     } else {
       const int e = ((it + 1) >> cpb_sh) == (it >> cpb_sh) ? list.get((it >> cpb_sh), lane) : list.peek_next((it >> cpb_sh));
-      kv0_n = (e >> 8) * S + (((it + 1) & cpb_m)) * kChunk;
+      kv0_n = (e >> 8) * S + (((it + 1) & cpb_m)) * CH;
     }
   };
 
-  const typename DmaTile<D>::Plan plan = DmaTile<D>::plan(p.kv_st, wave, lane);
-  const int trb = DmaTile<D>::tr_base(lane);
+  const typename Tile::Plan plan = Tile::plan(p.kv_st, wave, lane);
+  const int trb = Tile::tr_base(lane);
   if (total > 0) {
     int kv0;
     bool keep;
     chunk_of(0, kv0, keep);
-    DmaTile<D>::issue(plan, kb + (int64_t)kv0 * p.kv_st, sm.k[0], wave);
-    DmaTile<D>::issue(plan, vb + (int64_t)kv0 * p.kv_st, sm.v[0], wave);
+    Tile::issue(plan, kb + (int64_t)kv0 * p.kv_st, sm.k[0], wave);
+    Tile::issue(plan, vb + (int64_t)kv0 * p.kv_st, sm.v[0], wave);
   }
 
   bf16x8 qf[D / 16], gf[D / 16];  // Q^T and dO^T fragments (B operands), lane = query
@@ -167,8 +170,8 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
     if (it + 1 < total) {
       int kv1;
       next_chunk_of(it, kv1);
-      DmaTile<D>::issue(plan, kb + (int64_t)kv1 * p.kv_st, sm.k[buf ^ 1], wave);
-      DmaTile<D>::issue(plan, vb + (int64_t)kv1 * p.kv_st, sm.v[buf ^ 1], wave);
+      Tile::issue(plan, kb + (int64_t)kv1 * p.kv_st, sm.k[buf ^ 1], wave);
+      Tile::issue(plan, vb + (int64_t)kv1 * p.kv_st, sm.v[buf ^ 1], wave);
     }
 
     if (wave_active && keep && kv0 <= qw0 + 31) {
@@ -176,14 +179,14 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
       const uint16_t* vs = sm.v[buf];
       const int qpos = qw0 + l32;
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
+      for (int kt = 0; kt < KT; ++kt) {
         const int kbase = kv0 + 32 * kt;
         if (kbase > qw0 + 31) continue;  // every key of this half-chunk lies after my queries
         f32x16 s = f32x16{}, dp = f32x16{};
 #pragma unroll
-        for (int kk = 0; kk < D / 16; ++kk) s = mfma32(DmaTile<D>::row_frag(ks, kt, kk, l32, half), qf[kk], s);
+        for (int kk = 0; kk < D / 16; ++kk) s = mfma32(Tile::row_frag(ks, kt, kk, l32, half), qf[kk], s);
 #pragma unroll
-        for (int kk = 0; kk < D / 16; ++kk) dp = mfma32(DmaTile<D>::row_frag(vs, kt, kk, l32, half), gf[kk], dp);
+        for (int kk = 0; kk < D / 16; ++kk) dp = mfma32(Tile::row_frag(vs, kt, kk, l32, half), gf[kk], dp);
         const bool diag = kbase + 31 > qw0;
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = fast_exp2(__builtin_fmaf(s[r], c, -lse_l));
@@ -202,7 +205,7 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
                                    s[8 * u + 5], s[8 * u + 6], s[8 * u + 7]);
 #pragma unroll
           for (int dt = 0; dt < D / 32; ++dt)
-            acc[dt] = mfma32(DmaTile<D>::tr_frag(ks, dt, 2 * kt + u, trb), dsb, acc[dt]);
+            acc[dt] = mfma32(Tile::tr_frag(ks, dt, 2 * kt + u, trb), dsb, acc[dt]);
         }
       }
     }
@@ -226,20 +229,22 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
 
 // ------------------------------------------------------------------------------------ dk, dv
 
-template <int D>
+template <int D, int CH>
 struct DkvSmem {
-  uint16_t q[2][DmaTile<D>::kElems];
-  uint16_t g[2][DmaTile<D>::kElems];
+  uint16_t q[2][DmaTile<D, CH>::kElems];
+  uint16_t g[2][DmaTile<D, CH>::kElems];
   struct RowStats {
-    float delta[kChunk];
-    float lse[kChunk];     // base-2 units
+    float delta[CH];
+    float lse[CH];         // base-2 units
   } rs[2];                 // one 512-byte direct load fills both arrays of a stage
 };
 
-template <int D, bool DENSE>
+template <int D, bool DENSE, int CH>
 __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
+  typedef DmaTile<D, CH> Tile;
+  constexpr int QT = CH / 32;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  DkvSmem<D>& sm = *reinterpret_cast<DkvSmem<D>*>(smem_raw);
+  DkvSmem<D, CH>& sm = *reinterpret_cast<DkvSmem<D, CH>*>(smem_raw);
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -250,7 +255,7 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
   const int b = bh / p.heads, h = bh - b * p.heads;
   const int tile = DENSE ? rank : p.kv_tiles.order[h * T + rank];  // dense: first key tiles are longest
   const int S = DENSE ? kChunk : p.block_size;
-  const int cpb = S / kChunk;  // a power of two: / and % below are a shift and a mask
+  const int cpb = S / CH;  // a power of two: / and % below are a shift and a mask
   const int cpb_sh = __builtin_ctz(cpb), cpb_m = cpb - 1;
   const int N = p.seqlen;
 
@@ -287,36 +292,38 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
   // chunk `it` of the tile's list: its first row, and whether my mask row / column keeps it
   auto chunk_of = [&](int it, int& q0, bool& keep) {
     if (DENSE) {
-      q0 = N - kChunk - it * kChunk;  // from the last query chunk down, like the sparse lists
+      q0 = N - CH - it * CH;  // from the last query chunk down, like the sparse lists
       keep = true;
     } else {
       const int e = list.get((it >> cpb_sh), lane);
-      q0 = (e >> 8) * S + (cpb - 1 - (it & cpb_m)) * kChunk;
+      q0 = (e >> 8) * S + (cpb - 1 - (it & cpb_m)) * CH;
       keep = (e >> my_member) & 1;
     }
   };
   // first row of chunk it+1, right after chunk_of(it)
   auto next_chunk_of = [&](int it, int& q0_n) {
     if (DENSE) {
-      q0_n = N - kChunk - (it + 1) * kChunk;
+      q0_n = N - CH - (it + 1) * CH;
     } else {
       const int e = ((it + 1) >> cpb_sh) == (it >> cpb_sh) ? list.get((it >> cpb_sh), lane) : list.peek_next((it >> cpb_sh));
-      q0_n = (e >> 8) * S + (cpb - 1 - ((it + 1) & cpb_m)) * kChunk;
+      q0_n = (e >> 8) * S + (cpb - 1 - ((it + 1) & cpb_m)) * CH;
     }
   };
 
-  const typename DmaTile<D>::Plan plan = DmaTile<D>::plan(p.q_st, wave, lane);
+  const typename Tile::Plan plan = Tile::plan(p.q_st, wave, lane);
   const uint32_t stats_gap = (uint32_t)((const char*)lse_b - (const char*)delta_b);
   // `ln` is the lane number.  The loop passes a copy the optimiser cannot see through, so that
   // what is derived from it is recomputed each step (a few integer operations) rather than kept in
   // registers across the loop: this kernel has no registers to spare, and a spilled constant costs
   // a wait for all outstanding loads when it is fetched back.
   auto issue_chunk = [&](int q0, int buf, int ln) {
-    DmaTile<D>::issue(plan, qb + (int64_t)q0 * p.q_st, sm.q[buf], wave);
-    DmaTile<D>::issue(plan, gb + (int64_t)q0 * p.q_st, sm.g[buf], wave);
-    // 64 floats of each array = 2 x 256 bytes: lanes 0..15 fetch delta, lanes 16..31 lse, in one
-    // direct load issued by the wavefront that has one load fewer than the others in the two tiles
-    if (wave == 3 && ln < 32) dma16(delta_b + q0, 16 * ln + (ln < 16 ? 0u : stats_gap - 256u), lds_addr(&sm.rs[buf]));
+    Tile::issue(plan, qb + (int64_t)q0 * p.q_st, sm.q[buf], wave);
+    Tile::issue(plan, gb + (int64_t)q0 * p.q_st, sm.g[buf], wave);
+    // CH floats of each array: the first CH/4 lanes fetch delta, the next CH/4 lanes lse, 16 bytes
+    // each, in one direct load issued by the wavefront that has one load fewer than the others in the two tiles
+    constexpr int NL = CH / 4;  // lanes per array, 16 bytes each
+    if (wave == 3 && ln < 2 * NL)
+      dma16(delta_b + q0, 16 * ln + (ln < NL ? 0u : stats_gap - 16u * NL), lds_addr(&sm.rs[buf]));
   };
   if (total > 0) {
     int q0;
@@ -362,21 +369,21 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
       issue_chunk(q1, buf ^ 1, ln);
     }
 
-    if (wave_active && keep && q0 + kChunk - 1 >= kvw0) {
+    if (wave_active && keep && q0 + CH - 1 >= kvw0) {
       const uint16_t* qs = sm.q[buf];
       const uint16_t* gs = sm.g[buf];
       const int l32 = ln & 31, half = ln >> 5;
-      const int trb = DmaTile<D>::tr_base(ln);
+      const int trb = Tile::tr_base(ln);
       const int key = kvw0 + l32;
 #pragma unroll
-      for (int qt = 0; qt < 2; ++qt) {
+      for (int qt = 0; qt < QT; ++qt) {
         const int qbase = q0 + 32 * qt;
         if (qbase + 31 < kvw0) continue;  // every query of this half-chunk lies before my keys
         f32x16 s = f32x16{}, dp = f32x16{};
 #pragma unroll
-        for (int kk = 0; kk < D / 16; ++kk) s = mfma32(DmaTile<D>::row_frag(qs, qt, kk, l32, half), kf[kk], s);
+        for (int kk = 0; kk < D / 16; ++kk) s = mfma32(Tile::row_frag(qs, qt, kk, l32, half), kf[kk], s);
 #pragma unroll
-        for (int kk = 0; kk < D / 16; ++kk) dp = mfma32(DmaTile<D>::row_frag(gs, qt, kk, l32, half), vf[kk], dp);
+        for (int kk = 0; kk < D / 16; ++kk) dp = mfma32(Tile::row_frag(gs, qt, kk, l32, half), vf[kk], dp);
         const bool diag = qbase < kvw0 + 31;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
@@ -400,8 +407,8 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
                                    dp[8 * u + 5], dp[8 * u + 6], dp[8 * u + 7]);
 #pragma unroll
           for (int dt = 0; dt < D / 32; ++dt) {
-            acc_dv[dt] = mfma32(DmaTile<D>::tr_frag(gs, dt, 2 * qt + u, trb), pb, acc_dv[dt]);
-            acc_dk[dt] = mfma32(DmaTile<D>::tr_frag(qs, dt, 2 * qt + u, trb), dsb, acc_dk[dt]);
+            acc_dv[dt] = mfma32(Tile::tr_frag(gs, dt, 2 * qt + u, trb), pb, acc_dv[dt]);
+            acc_dk[dt] = mfma32(Tile::tr_frag(qs, dt, 2 * qt + u, trb), dsb, acc_dk[dt]);
           }
         }
       }
@@ -438,12 +445,12 @@ hipError_t set_smem(K kernel, size_t bytes, bool& done) {
   return e;
 }
 
-template <int D, bool DENSE>
+template <int D, bool DENSE, int CH>
 hipError_t launch_one(const AttnParams& p, int stages, hipStream_t stream) {
   static bool dq_set = false, dkdv_set = false;
-  hipError_t e = set_smem(&dq_kernel<D, DENSE>, sizeof(DqSmem<D>), dq_set);
+  hipError_t e = set_smem(&dq_kernel<D, DENSE, CH>, sizeof(DqSmem<D, CH>), dq_set);
   if (e != hipSuccess) return e;
-  e = set_smem(&dkdv_kernel<D, DENSE>, sizeof(DkvSmem<D>), dkdv_set);
+  e = set_smem(&dkdv_kernel<D, DENSE, CH>, sizeof(DkvSmem<D, CH>), dkdv_set);
   if (e != hipSuccess) return e;
 
   const int64_t rows = (int64_t)p.batch * p.heads * p.seqlen;
@@ -455,14 +462,14 @@ hipError_t launch_one(const AttnParams& p, int stages, hipStream_t stream) {
   }
   const int bh = p.batch * p.heads;
   if (stages & kBwdDkDv) {
-    hipLaunchKernelGGL((dkdv_kernel<D, DENSE>), dim3(grid_for(bh, p.kv_tiles.tiles_per_head)),
-                       dim3(kThreads), sizeof(DkvSmem<D>), stream, p);
+    hipLaunchKernelGGL((dkdv_kernel<D, DENSE, CH>), dim3(grid_for(bh, p.kv_tiles.tiles_per_head)),
+                       dim3(kThreads), sizeof(DkvSmem<D, CH>), stream, p);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   if (stages & kBwdDq) {
-    hipLaunchKernelGGL((dq_kernel<D, DENSE>), dim3(grid_for(bh, p.q_tiles.tiles_per_head)), dim3(kThreads),
-                       sizeof(DqSmem<D>), stream, p);
+    hipLaunchKernelGGL((dq_kernel<D, DENSE, CH>), dim3(grid_for(bh, p.q_tiles.tiles_per_head)), dim3(kThreads),
+                       sizeof(DqSmem<D, CH>), stream, p);
     e = hipGetLastError();
   }
   return e;
@@ -471,9 +478,12 @@ hipError_t launch_one(const AttnParams& p, int stages, hipStream_t stream) {
 }  // namespace
 
 hipError_t launch_bwd(const AttnParams& p, bool dense, int stages, hipStream_t stream) {
+  // 32-token mask blocks are walked in steps of 32 rows, everything else in steps of 64
+  if (!dense && p.block_size == 32)
+    return p.head_dim == 128 ? launch_one<128, false, 32>(p, stages, stream) : launch_one<64, false, 32>(p, stages, stream);
   if (p.head_dim == 128)
-    return dense ? launch_one<128, true>(p, stages, stream) : launch_one<128, false>(p, stages, stream);
-  return dense ? launch_one<64, true>(p, stages, stream) : launch_one<64, false>(p, stages, stream);
+    return dense ? launch_one<128, true, kChunk>(p, stages, stream) : launch_one<128, false, kChunk>(p, stages, stream);
+  return dense ? launch_one<64, true, kChunk>(p, stages, stream) : launch_one<64, false, kChunk>(p, stages, stream);
 }
 
 }  // namespace s2

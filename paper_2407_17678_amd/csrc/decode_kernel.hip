@@ -76,7 +76,8 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(const DecodeParams
   L = min(max(L, 1), p.max_len);
   const int32_t* table = PAGED ? p.block_table + ((int64_t)b * p.heads + h) * p.max_blocks : nullptr;
   const int S = p.block_size;
-  const int cpb = S / kChunk;
+  const int U = min(S, kChunk);  // tokens per unit of work: 64, or a whole block when it is shorter
+  const int cpb = S / U;
   const int i = (L - 1) / S;
   const RowBlocks rb = row_blocks(p, h, i);
   const int units = rb.count * cpb;
@@ -102,7 +103,8 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(const DecodeParams
 
   for (int u = u_lo + wave; u < u_hi; u += 4) {
     const int blk = rb.block(u / cpb);
-    const int tok0 = blk * S + (u % cpb) * kChunk;
+    const int tok0 = blk * S + (u % cpb) * U;
+    const int tok_end = min(L, tok0 + U);  // a 32-token block fills half of the 64 rows loaded
     if (tok0 >= L) continue;  // second half of a partial last block
     // row `tok` of the cache is at base + (tok - shift) * kv_st
     int64_t base = 0;
@@ -119,12 +121,12 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(const DecodeParams
     bf16x8 kr[NI], vr[NI];
 #pragma unroll
     for (int n = 0; n < NI; ++n) {
-      const int tok = min(tok0 + RPI * n + g, L - 1);  // clamp: never read past the sequence
+      const int tok = min(tok0 + RPI * n + g, tok_end - 1);  // clamp: never read past the unit
       kr[n] = *reinterpret_cast<const bf16x8*>(kb + base + (int64_t)(tok - shift) * p.kv_st);
     }
 #pragma unroll
     for (int n = 0; n < NI; ++n) {
-      const int tok = min(tok0 + RPI * n + g, L - 1);
+      const int tok = min(tok0 + RPI * n + g, tok_end - 1);
       vr[n] = *reinterpret_cast<const bf16x8*>(vb + base + (int64_t)(tok - shift) * p.kv_st);
     }
     float s[NI];
@@ -136,7 +138,7 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(const DecodeParams
       for (int e = 0; e < 8; ++e) d = __builtin_fmaf(qv[e], (float)kr[n][e], d);
 #pragma unroll
       for (int m = 1; m < LPR; m <<= 1) d += __shfl_xor(d, m, 64);
-      if (tok0 + RPI * n + g >= L) d = kNegInf;
+      if (tok0 + RPI * n + g >= tok_end) d = kNegInf;
       s[n] = d;
       mx = fmaxf(mx, d);
     }

@@ -241,7 +241,10 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
 template <int D, bool DENSE>
 hipError_t launch_one(const AttnParams& p, hipStream_t stream) {
   const int grid = grid_for(p.batch * p.heads, (p.q_rows + kFwdBM - 1) / kFwdBM);
-  hipLaunchKernelGGL((fwd_kernel<D, DENSE, kFwdChunk>), dim3(grid), dim3(kThreads), 0, stream, p);
+  if (!DENSE && p.block_size == 32)  // 32-token mask blocks: steps of 32 keys
+    hipLaunchKernelGGL((fwd_kernel<D, false, 32>), dim3(grid), dim3(kThreads), 0, stream, p);
+  else
+    hipLaunchKernelGGL((fwd_kernel<D, DENSE, kFwdChunk>), dim3(grid), dim3(kThreads), 0, stream, p);
   return hipGetLastError();
 }
 

@@ -85,7 +85,7 @@ int64_t row_blocks(const s2_layout_params& p, int head, int i, int32_t* out, int
 
 int build_host(const s2_layout_params& p, s2_layout& L) {
   if (p.num_heads < 1 || p.num_blocks < 1 || p.head_index_base < 0) return S2_ERR_BAD_PARAM;
-  if (p.block_size != 64 && p.block_size != 128) return S2_ERR_BAD_PARAM;
+  if (p.block_size != 32 && p.block_size != 64 && p.block_size != 128) return S2_ERR_BAD_PARAM;
   if (!p.dense && (p.local_blocks < 1 || p.stride < 0 || p.window_blocks < 0)) return S2_ERR_BAD_PARAM;
   if (p.dense != 0 && p.dense != 1) return S2_ERR_BAD_PARAM;
   const int H = p.num_heads, B = p.num_blocks;
@@ -139,7 +139,7 @@ int build_host(const s2_layout_params& p, s2_layout& L) {
 int build_from_csr(int num_heads, int num_blocks, int block_size, const int32_t* row_ptr,
                    const int32_t* col_idx, s2_layout& L) {
   if (num_heads < 1 || num_blocks < 1) return S2_ERR_BAD_PARAM;
-  if (block_size != 64 && block_size != 128) return S2_ERR_BAD_PARAM;
+  if (block_size != 32 && block_size != 64 && block_size != 128) return S2_ERR_BAD_PARAM;
   const int H = num_heads, B = num_blocks;
   if ((int64_t)H * B + 1 > std::numeric_limits<int32_t>::max()) return S2_ERR_OVERFLOW;
   if ((int64_t)B * block_size > std::numeric_limits<int32_t>::max()) return S2_ERR_OVERFLOW;

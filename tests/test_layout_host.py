@@ -58,7 +58,7 @@ def test_layout_bit_exact_random_parameters():
     for _ in range(120):
         H = int(rng.integers(1, 10))
         Bk = int(rng.integers(1, 70))
-        S = int(rng.choice([64, 128]))
+        S = int(rng.choice([32, 64, 128]))
         B_l = int(rng.integers(1, 9))
         s = int(rng.integers(0, 12))
         base = int(rng.integers(0, 20))
@@ -77,7 +77,7 @@ def test_layout_variants():
 
 
 @pytest.mark.parametrize("kw,code", [
-    (dict(num_heads=0), -2), (dict(num_blocks=0), -2), (dict(block_size=32), -2),
+    (dict(num_heads=0), -2), (dict(num_blocks=0), -2), (dict(block_size=16), -2), (dict(block_size=96), -2),
     (dict(local_blocks=0), -2), (dict(stride=-1), -2), (dict(window_blocks=-1), -2),
     (dict(head_index_base=-1), -2), (dict(dense=2), -2),
 ])
@@ -183,7 +183,7 @@ def test_resident_blocks_bit_exact_against_the_oracle():
             assert B.s2_kv_resident_blocks(p, h, L) == orc.resident_blocks(L, h, 64, w.local_blocks, w.stride)
     rng = np.random.default_rng(5)
     for _ in range(150):
-        S = int(rng.choice([64, 128]))
+        S = int(rng.choice([32, 64, 128]))
         H = int(rng.integers(1, 9))
         B_l = int(rng.integers(1, 7))
         s = int(rng.integers(0, 9))
@@ -207,7 +207,7 @@ def test_resident_blocks_errors():
     assert lib.s2_kv_resident_blocks(C.byref(p), 4, 10, buf, 2, C.byref(n)) == -2   # head out of range
     assert lib.s2_kv_resident_blocks(C.byref(p), -1, 10, buf, 2, C.byref(n)) == -2
     assert lib.s2_kv_resident_blocks(C.byref(p), 0, 0, buf, 2, C.byref(n)) == -2    # length < 1
-    bad = B.layout_params(4, 1, 32, 2, 4)
+    bad = B.layout_params(4, 1, 16, 2, 4)
     assert lib.s2_kv_resident_blocks(C.byref(bad), 0, 10, buf, 2, C.byref(n)) == -2
     # capacity too small: count still reported, first entries written
     assert lib.s2_kv_resident_blocks(C.byref(p), 0, 64 * 8, buf, 2, C.byref(n)) == -8
@@ -259,7 +259,7 @@ def test_layout_from_csr_round_trip_and_transpose():
         H, Bk, _ = M.shape
         assert orc.valid_custom_mask(M)
         row_ptr, col_idx, col_ptr, row_idx = orc.compressed_layout(M)
-        for S in (64, 128):
+        for S in (32, 64, 128):
             lay = B.s2_layout_from_csr(H, Bk, S, row_ptr, col_idx)
             got = B.s2_layout_get(lay)
             assert got["nnz"] == int(M.sum()) and got["block_size"] == S
@@ -284,7 +284,7 @@ def test_layout_from_csr_rejects_bad_rows():
     assert lib.s2_layout_from_csr(1, 3, 64, arr(good_rp), arr(good_ci), None) == -1
     assert call(0, 3, 64, good_rp, good_ci) == -2
     assert call(1, 0, 64, good_rp, good_ci) == -2
-    assert call(1, 3, 32, good_rp, good_ci) == -2
+    assert call(1, 3, 48, good_rp, good_ci) == -2
     assert call(1, 3, 64, [1, 2, 4, 6], good_ci + [0]) == -2        # row_ptr[0] != 0
     assert call(1, 3, 64, [0, 1, 1, 3], [0, 0, 2]) == -2            # empty row
     assert call(1, 3, 64, [0, 1, 3, 5], [0, 1, 1, 0, 2]) == -2      # not strictly ascending
