@@ -117,9 +117,11 @@ def bench_train(w, steps, warmup, with_dense=True, with_bwd=True, dense_steps=3,
     res["ms_fwd"] = time_events(fwd, steps, 1)
     flops_fwd = 4.0 * D * pairs
     if with_bwd:
-        res["ms_bwd_delta"] = time_events(stage(B.BWD_DELTA), steps, 1)
-        res["ms_bwd_dkdv"] = time_events(stage(B.BWD_DKDV), steps, 1)
+        # the backward is the dQ launch (which also computes delta) followed by the dK/dV launch
         res["ms_bwd_dq"] = time_events(stage(B.BWD_DQ), steps, 1)
+        res["ms_bwd_dkdv"] = time_events(stage(B.BWD_DKDV), steps, 1)
+        # the stand-alone delta kernel, only used when dK/dV is asked for without dQ: not in a step
+        res["ms_delta_standalone"] = time_events(stage(B.BWD_DELTA), steps, 1)
         flops = 14.0 * D * pairs
     else:
         flops = flops_fwd

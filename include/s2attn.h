@@ -183,11 +183,12 @@ int s2_attn_bwd(const s2_layout* layout, const s2_tensors* t, float scale, void*
                 size_t workspace_bytes, void* stream);
 size_t s2_attn_bwd_workspace_bytes(int32_t batch, int32_t heads, int32_t seqlen, int32_t head_dim);
 
-/* The backward is three launches: delta = rowsum(dO*O) into the workspace, then dK/dV, then dQ
- * (the last two only read delta).  This variant runs the subset named by `stages` (an OR of the
- * flags below) so that a profiler or a benchmark can time each launch on its own; with
- * S2_BWD_ALL it is s2_attn_bwd.  Running S2_BWD_DKDV or S2_BWD_DQ requires that S2_BWD_DELTA has
- * run on the same workspace before.  Errors as s2_attn_bwd, plus BAD_PARAM for stages. */
+/* The backward is two launches: dQ (which also computes delta = rowsum(dO*O) and leaves it in
+ * the workspace), then dK/dV (which reads delta).  This variant runs the subset named by `stages`
+ * (an OR of the flags below) so that a profiler or a benchmark can time each launch on its own;
+ * with S2_BWD_ALL it is s2_attn_bwd.  S2_BWD_DKDV needs delta in the workspace: from S2_BWD_DQ in
+ * the same or an earlier call, or from S2_BWD_DELTA, a stand-alone delta kernel that only runs
+ * when S2_BWD_DQ is not part of the call.  Errors as s2_attn_bwd, plus BAD_PARAM for stages. */
 enum { S2_BWD_DELTA = 1, S2_BWD_DKDV = 2, S2_BWD_DQ = 4, S2_BWD_ALL = 7 };
 int s2_attn_bwd_stages(const s2_layout* layout, const s2_tensors* t, float scale, void* workspace,
                        size_t workspace_bytes, int stages, void* stream);

@@ -1,8 +1,9 @@
 // Backward kernels: gradients of block-sparse causal attention (the backward pass that goes with
 // the forward of section 3.2; the paper names it as the less optimised half of its kernels).
 //
-// Three launches, no atomics, bitwise reproducible:
-//   delta  : delta[t] = sum_d dO[t][d] * O[t][d]
+// Two launches (three kernels exist), no atomics, bitwise reproducible:
+//   delta  : delta[t] = sum_d dO[t][d] * O[t][d].  Folded into the dq launch, which holds the dO
+//            fragments anyway; the stand-alone kernel runs only when dK/dV is asked for alone.
 //   dq     : row-stationary.  A workgroup owns 128 query rows and walks the merged list of KV
 //            blocks its mask rows keep (as the forward does), recomputing P and forming
 //            dS = P * (dP - delta), dQ += scale * dS K.
@@ -137,21 +138,33 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
 
   bf16x8 qf[D / 16], gf[D / 16];  // Q^T and dO^T fragments (B operands), lane = query
   float lse_l = 0.f, delta_l = 0.f;
+  // delta = rowsum(dO * O) of my query, computed here from the dO fragments the kernel holds
+  // anyway (my half of the row's features, then the two halves added), so that a whole backward
+  // needs no separate pass over O and dO; it is also written out, with LSE in base-2 units, for
+  // the dK/dV kernel, which runs after this one.
+  float part = 0.f;
 #pragma unroll
   for (int kk = 0; kk < D / 16; ++kk) {
     if (wave_active) {
       const int64_t o = q_off + (int64_t)(qw0 + l32) * p.q_st + 16 * kk + 8 * half;
       qf[kk] = *reinterpret_cast<const bf16x8*>(p.q + o);
       gf[kk] = *reinterpret_cast<const bf16x8*>(p.d_o + o);
+      const bf16x8 of = *reinterpret_cast<const bf16x8*>(p.o + o);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) part = __builtin_fmaf((float)gf[kk][e], (float)of[e], part);
     } else {
       qf[kk] = bf16x8{};
       gf[kk] = bf16x8{};
     }
   }
+  delta_l = sum_halves(part);
   if (wave_active) {
     const int64_t r = ((int64_t)b * p.heads + h) * N + qw0 + l32;
-    lse_l = p.lse2[r];
-    delta_l = p.delta[r];
+    lse_l = p.lse[r] * kLog2e;
+    if (half == 0) {
+      p.delta[r] = delta_l;
+      p.lse2[r] = lse_l;
+    }
   }
 
   f32x16 acc[D / 32];
@@ -455,21 +468,23 @@ hipError_t launch_one(const AttnParams& p, int stages, hipStream_t stream) {
 
   const int64_t rows = (int64_t)p.batch * p.heads * p.seqlen;
   constexpr int RPB = 256 / (D / 8);
-  if (stages & kBwdDelta) {
+  // The dQ kernel computes delta itself and leaves it (and LSE in base-2 units) in the workspace,
+  // so it runs first and the stand-alone delta kernel only when dQ is not part of the call.
+  if ((stages & kBwdDelta) && !(stages & kBwdDq)) {
     hipLaunchKernelGGL((delta_kernel<D>), dim3((unsigned)((rows + RPB - 1) / RPB)), dim3(256), 0, stream, p);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   const int bh = p.batch * p.heads;
-  if (stages & kBwdDkDv) {
-    hipLaunchKernelGGL((dkdv_kernel<D, DENSE, CH>), dim3(grid_for(bh, p.kv_tiles.tiles_per_head)),
-                       dim3(kThreads), sizeof(DkvSmem<D, CH>), stream, p);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
   if (stages & kBwdDq) {
     hipLaunchKernelGGL((dq_kernel<D, DENSE, CH>), dim3(grid_for(bh, p.q_tiles.tiles_per_head)), dim3(kThreads),
                        sizeof(DqSmem<D, CH>), stream, p);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  if (stages & kBwdDkDv) {
+    hipLaunchKernelGGL((dkdv_kernel<D, DENSE, CH>), dim3(grid_for(bh, p.kv_tiles.tiles_per_head)),
+                       dim3(kThreads), sizeof(DkvSmem<D, CH>), stream, p);
     e = hipGetLastError();
   }
   return e;
