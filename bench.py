@@ -35,6 +35,17 @@ def sparse_pairs(nnz, H, B, S):
     return (nnz - H * B) * S * S + H * B * S * (S + 1) // 2
 
 
+def prewarm(fn, seconds=0.3):
+    """Untimed: runs fn until the GPU has been busy for a while, so that what is measured next is
+    at the sustained clocks of a long-running job rather than those of a device just woken up."""
+    import torch
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(8):
+            fn()
+        torch.cuda.synchronize()
+
+
 def time_events(fn, steps, warmup):
     import torch
     for _ in range(warmup):
@@ -96,7 +107,26 @@ def bench_train(w, steps, warmup, with_dense=True, with_bwd=True, dense_steps=3,
         if with_bwd:
             bwd()
 
-    # the timed region: exactly `steps` steps between two synchronisations
+    # Untimed: bring the GPU to its sustained clocks first (whatever is measured in the first tens of
+    # milliseconds after idle comes out 3-12 % slow), as it would be in a long-running job.
+    prewarm(step)
+
+    res = dict(workload=w.name, batch=Bt, heads=H, seqlen=N, head_dim=D, block_size=S,
+               local_blocks=w.local_blocks, stride=w.stride, nnz_blocks=int(nnz),
+               layout_build_ms=round(layout_ms, 2))
+    # each kernel on its own (same stream, same inputs)
+    res["ms_fwd"] = time_events(fwd, steps, 1)
+    flops_fwd = 4.0 * D * pairs
+    if with_bwd:
+        # the backward is the dQ launch (which also computes delta) followed by the dK/dV launch
+        res["ms_bwd_dq"] = time_events(stage(B.BWD_DQ), steps, 1)
+        res["ms_bwd_dkdv"] = time_events(stage(B.BWD_DKDV), steps, 1)
+        # the stand-alone delta kernel, only used when dK/dV is asked for without dQ: not in a step
+        res["ms_delta_standalone"] = time_events(stage(B.BWD_DELTA), steps, 1)
+        flops = 14.0 * D * pairs
+    else:
+        flops = flops_fwd
+    # the timed region: `warmup` untimed steps, then exactly `steps` steps between two synchronisations
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
@@ -110,21 +140,8 @@ def bench_train(w, steps, warmup, with_dense=True, with_bwd=True, dense_steps=3,
     wall_ms = (time.perf_counter() - t_wall) * 1e3 / steps
     ms_step = e0.elapsed_time(e1) / steps
 
-    res = dict(workload=w.name, batch=Bt, heads=H, seqlen=N, head_dim=D, block_size=S,
-               local_blocks=w.local_blocks, stride=w.stride, nnz_blocks=int(nnz),
-               layout_build_ms=round(layout_ms, 2), ms_per_step=ms_step, wall_ms_per_step=wall_ms)
-    # each kernel on its own (same stream, same inputs)
-    res["ms_fwd"] = time_events(fwd, steps, 1)
-    flops_fwd = 4.0 * D * pairs
-    if with_bwd:
-        # the backward is the dQ launch (which also computes delta) followed by the dK/dV launch
-        res["ms_bwd_dq"] = time_events(stage(B.BWD_DQ), steps, 1)
-        res["ms_bwd_dkdv"] = time_events(stage(B.BWD_DKDV), steps, 1)
-        # the stand-alone delta kernel, only used when dK/dV is asked for without dQ: not in a step
-        res["ms_delta_standalone"] = time_events(stage(B.BWD_DELTA), steps, 1)
-        flops = 14.0 * D * pairs
-    else:
-        flops = flops_fwd
+    res["ms_per_step"] = ms_step
+    res["wall_ms_per_step"] = wall_ms
     res["effective_gflop"] = flops / 1e9
     res["tflops"] = flops / (ms_step * 1e-3) / 1e12
     res["tflops_fwd"] = flops_fwd / (res["ms_fwd"] * 1e-3) / 1e12
@@ -264,6 +281,7 @@ def bench_decode_paged(w, steps, warmup):
                      device="cuda")
     run = lambda: B.s2_attn_decode_paged(p, q, kp, vp, tb, sl, o, lse, w.scale, ws, missing=missing,
                                          num_splits=splits)
+    prewarm(run)
     ms = time_events(run, steps, warmup)
     if int(missing.item()) != 0:
         sys.exit("bench.py: the paged decode found kept blocks missing from its own table")
@@ -306,6 +324,7 @@ def bench_decode(w, steps, warmup):
     ws = torch.empty(B.s2_attn_decode_workspace_bytes(nseq, H, D, max_len, splits), dtype=torch.uint8,
                      device="cuda")
     run = lambda: B.s2_attn_decode(p, q, kc, vc, sl, o, lse, w.scale, ws, max_len, num_splits=splits)
+    prewarm(run)
     ms = time_events(run, steps, warmup)
     # algorithmic bytes: K and V rows of the kept tokens, plus q, o and the split partials
     S = w.block_size
