@@ -40,7 +40,8 @@ enum {
   S2_ERR_ALIGN = -4,      /* pointer or stride not 16-byte aligned                       */
   S2_ERR_WORKSPACE = -5,  /* workspace missing or too small                              */
   S2_ERR_HIP = -6,        /* a HIP runtime call failed; see s2_last_hip_error()          */
-  S2_ERR_NO_DEVICE = -7,  /* layout was built without a GPU and a launch was requested   */
+  S2_ERR_NO_DEVICE = -7,  /* layout has no copy on the current device (built without a GPU,
+                             or with another device current)                             */
   S2_ERR_OVERFLOW = -8    /* index arrays would not fit in int32                         */
 };
 

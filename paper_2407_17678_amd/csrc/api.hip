@@ -107,6 +107,17 @@ s2::AttnParams make_params(const s2_tensors* t, float scale) {
   return p;
 }
 
+// The layout's lists live on the device that was current when it was built.
+bool layout_on_current_device(const s2_layout* L) {
+  if (!L->on_device) return false;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return dev == L->device;
+}
+
 int check_layout_fits(const s2_layout* L, const s2_tensors* t) {
   if (!L) return S2_ERR_NULL;
   if (t->heads != L->p.num_heads) return S2_ERR_SHAPE;
@@ -220,7 +231,7 @@ int s2_attn_fwd(const s2_layout* layout, const s2_tensors* t, float scale, void*
   if (st != S2_OK) return st;
   st = check_layout_fits(layout, t);
   if (st != S2_OK) return st;
-  if (!layout->on_device) return S2_ERR_NO_DEVICE;
+  if (!layout_on_current_device(layout)) return S2_ERR_NO_DEVICE;
   s2::AttnParams p = make_params(t, scale);
   p.block_size = layout->p.block_size;
   p.fwd_tiles = dev_tiles(layout->fwd_tiles);
@@ -252,7 +263,7 @@ int s2_attn_fwd_rows(const s2_layout* layout, const s2_tensors* t, int32_t q_row
   if (q_row_start < 0 || q_rows < s2::kFwdBM || q_row_start % s2::kFwdBM != 0 || q_rows % s2::kFwdBM != 0)
     return S2_ERR_SHAPE;
   if ((int64_t)q_row_start + q_rows > t->seqlen) return S2_ERR_SHAPE;
-  if (!layout->on_device) return S2_ERR_NO_DEVICE;
+  if (!layout_on_current_device(layout)) return S2_ERR_NO_DEVICE;
   s2::AttnParams p = make_params(t, scale);
   p.q_row0 = q_row_start;
   p.q_rows = q_rows;
@@ -274,7 +285,7 @@ int s2_attn_bwd_stages(const s2_layout* layout, const s2_tensors* t, float scale
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 ||
       workspace_bytes < s2_attn_bwd_workspace_bytes(t->batch, t->heads, t->seqlen, t->head_dim))
     return S2_ERR_WORKSPACE;
-  if (!layout->on_device) return S2_ERR_NO_DEVICE;
+  if (!layout_on_current_device(layout)) return S2_ERR_NO_DEVICE;
   s2::AttnParams p = make_params(t, scale);
   p.delta = static_cast<float*>(workspace);
   p.lse2 = p.delta + s2_attn_bwd_workspace_bytes(t->batch, t->heads, t->seqlen, t->head_dim) / 8;
