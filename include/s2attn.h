@@ -50,7 +50,7 @@ typedef struct {
   int32_t num_heads;       /* H: heads covered by this layout (>= 1)                          */
   int32_t head_index_base; /* global index of local head 0; o_h uses the global index (>= 0)  */
   int32_t num_blocks;      /* B = N / S (>= 1)                                                */
-  int32_t block_size;      /* S in tokens: 32, 64 or 128                                      */
+  int32_t block_size;      /* S in tokens: 16, 32, 64 or 128 (16: num_blocks must be even)   */
   int32_t local_blocks;    /* B_l >= 1; counts the diagonal block                             */
   int32_t stride;          /* s >= 0; 0 = no stripes (pure sliding window)                    */
   int32_t window_blocks;   /* upper bound on i-j for stripes; 0 = unbounded                   */
@@ -139,8 +139,9 @@ typedef struct {
 
 /* Builds the per-head lists of kept KV blocks from the closed form of the mask, on the host,
  * and, when a GPU is visible, uploads them to the current device.  *out is owned by the
- * caller until s2_layout_destroy.  Errors: NULL, BAD_PARAM (H<1, B<1, S not 32/64/128, B_l<1,
- * stride<0, window<0, head_index_base<0), OVERFLOW, HIP. */
+ * caller until s2_layout_destroy.  Errors: NULL, BAD_PARAM (H<1, B<1, S not 16/32/64/128, S = 16
+ * with odd B, B_l<1, stride<0, window<0, head_index_base<0), OVERFLOW (more than 32768 blocks, or
+ * 65536 16-token ones; list sizes beyond int32), HIP. */
 int s2_layout_build(const s2_layout_params* params, s2_layout** out);
 /* A layout from the caller's own per-head pattern instead of the section 4.2 rule (section 3
  * promises patterns customised per head and per context range; section 5.1 compares several:
@@ -150,7 +151,7 @@ int s2_layout_build(const s2_layout_params* params, s2_layout** out);
  * the row's own index (causal) and the row's own index last (a token always attends its own
  * block, so no softmax is empty).  The arrays are copied.  The result works with s2_attn_fwd /
  * s2_attn_bwd; decode takes its pattern from s2_layout_params and has no such variant.
- * Errors: NULL, BAD_PARAM (H<1, B<1, S not 32/64/128, or a row breaking the rules above), OVERFLOW,
+ * Errors: NULL, BAD_PARAM (H<1, B<1, S not 16/32/64/128, S = 16 with odd B, or a row breaking the rules above), OVERFLOW,
  * HIP. */
 int s2_layout_from_csr(int32_t num_heads, int32_t num_blocks, int32_t block_size,
                        const int32_t* row_ptr, const int32_t* col_idx, s2_layout** out);

@@ -357,7 +357,7 @@ int s2_attn_decode(const s2_layout_params* lp, const s2_decode_args* a, float sc
   if (!lp || !a) return S2_ERR_NULL;
   if (!a->q || !a->k_cache || !a->v_cache || !a->seq_lens || !a->o) return S2_ERR_NULL;
   if (!(scale > 0.f) || !std::isfinite(scale)) return S2_ERR_BAD_PARAM;
-  if (lp->block_size != 32 && lp->block_size != 64 && lp->block_size != 128) return S2_ERR_BAD_PARAM;
+  if (lp->block_size != 16 && lp->block_size != 32 && lp->block_size != 64 && lp->block_size != 128) return S2_ERR_BAD_PARAM;
   if (lp->dense != 0 && lp->dense != 1) return S2_ERR_BAD_PARAM;
   if (!lp->dense && (lp->local_blocks < 1 || lp->stride < 0 || lp->window_blocks < 0)) return S2_ERR_BAD_PARAM;
   if (lp->head_index_base < 0) return S2_ERR_BAD_PARAM;
@@ -412,7 +412,7 @@ int s2_attn_decode_paged(const s2_layout_params* lp, const s2_paged_decode_args*
   if (!lp || !a) return S2_ERR_NULL;
   if (!a->q || !a->k_pages || !a->v_pages || !a->block_table || !a->seq_lens || !a->o) return S2_ERR_NULL;
   if (!(scale > 0.f) || !std::isfinite(scale)) return S2_ERR_BAD_PARAM;
-  if (lp->block_size != 32 && lp->block_size != 64 && lp->block_size != 128) return S2_ERR_BAD_PARAM;
+  if (lp->block_size != 16 && lp->block_size != 32 && lp->block_size != 64 && lp->block_size != 128) return S2_ERR_BAD_PARAM;
   if (lp->dense != 0 && lp->dense != 1) return S2_ERR_BAD_PARAM;
   if (!lp->dense && (lp->local_blocks < 1 || lp->stride < 0 || lp->window_blocks < 0)) return S2_ERR_BAD_PARAM;
   if (lp->head_index_base < 0) return S2_ERR_BAD_PARAM;
@@ -473,7 +473,7 @@ int s2_kv_resident_blocks(const s2_layout_params* lp, int32_t head, int32_t leng
                           int32_t capacity, int32_t* count) {
   if (!lp || !count) return S2_ERR_NULL;
   if (capacity < 0 || (capacity > 0 && !blocks)) return S2_ERR_NULL;
-  if (lp->block_size != 32 && lp->block_size != 64 && lp->block_size != 128) return S2_ERR_BAD_PARAM;
+  if (lp->block_size != 16 && lp->block_size != 32 && lp->block_size != 64 && lp->block_size != 128) return S2_ERR_BAD_PARAM;
   if (lp->dense != 0 && lp->dense != 1) return S2_ERR_BAD_PARAM;
   if (!lp->dense && (lp->local_blocks < 1 || lp->stride < 0 || lp->window_blocks < 0)) return S2_ERR_BAD_PARAM;
   if (lp->head_index_base < 0 || lp->num_heads < 1) return S2_ERR_BAD_PARAM;

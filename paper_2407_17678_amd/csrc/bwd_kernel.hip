@@ -83,12 +83,16 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
   const int b = bh / p.heads, h = bh - b * p.heads;
   const int tile = DENSE ? (T - 1 - rank) : p.q_tiles.order[h * T + rank];
   const int S = DENSE ? kChunk : p.block_size;
-  const int cpb = S / CH;  // a power of two: / and % below are a shift and a mask
+  // 16-token blocks: a list entry is a unit of two blocks (32 keys, one step) and my 32 query rows
+  // are two mask rows, so which keys a lane may see is a 2 x 2 pattern of bits per wavefront
+  const bool fine = !DENSE && CH == 32 && S == 16;
+  const int Sg = fine ? 32 : S;  // tokens per list entry
+  const int cpb = Sg / CH;  // a power of two: / and % below are a shift and a mask
   const int cpb_sh = __builtin_ctz(cpb), cpb_m = cpb - 1;
   const int N = p.seqlen;
   const int qw0 = tile * kBwdBM + wave * 32;
   const bool wave_active = qw0 < N;
-  const int my_member = (qw0 / S) - tile * (kBwdBM / S);
+  const int my_member = (qw0 / Sg) - tile * (kBwdBM / Sg);
 
   const int64_t q_off = b * p.q_sb + h * p.q_sh;
   const int64_t kv_off = b * p.kv_sb + h * p.kv_sh;
@@ -106,14 +110,21 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
   EntryList list;
   if (!DENSE) list.init(p.q_tiles.ent + ent_lo, n_ent, lane);
   // chunk `it` of the tile's list: its first row, and whether my mask row / column keeps it
-  auto chunk_of = [&](int it, int& kv0, bool& keep) {
+  // `pat` (16-token blocks only): bit 2m + c set when mask row m of my two keeps block c of the unit
+  auto chunk_of = [&](int it, int& kv0, bool& keep, int& pat) {
+    pat = 0xF;
     if (DENSE) {
       kv0 = it * CH;
       keep = true;
     } else {
       const int e = list.get((it >> cpb_sh), lane);
-      kv0 = (e >> 8) * S + ((it & cpb_m)) * CH;
-      keep = (e >> my_member) & 1;
+      kv0 = (e >> 16) * Sg + ((it & cpb_m)) * CH;
+      if (fine) {
+        pat = (e >> (4 * wave)) & 0xF;
+        keep = pat != 0;
+      } else {
+        keep = (e >> my_member) & 1;
+      }
     }
   };
   // first row of chunk it+1, right after chunk_of(it)
@@ -122,16 +133,16 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
       kv0_n = (it + 1) * CH;
     } else {
       const int e = ((it + 1) >> cpb_sh) == (it >> cpb_sh) ? list.get((it >> cpb_sh), lane) : list.peek_next((it >> cpb_sh));
-      kv0_n = (e >> 8) * S + (((it + 1) & cpb_m)) * CH;
+      kv0_n = (e >> 16) * Sg + (((it + 1) & cpb_m)) * CH;
     }
   };
 
   const typename Tile::Plan plan = Tile::plan(p.kv_st, wave, lane);
   const int trb = Tile::tr_base(lane);
   if (total > 0) {
-    int kv0;
+    int kv0, pat;
     bool keep;
-    chunk_of(0, kv0, keep);
+    chunk_of(0, kv0, keep, pat);
     Tile::issue(plan, kb + (int64_t)kv0 * p.kv_st, sm.k[0], wave);
     Tile::issue(plan, vb + (int64_t)kv0 * p.kv_st, sm.v[0], wave);
   }
@@ -177,9 +188,9 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
 
   for (int it = 0; it < total; ++it) {
     const int buf = it & 1;
-    int kv0;
+    int kv0, pat;
     bool keep;
-    chunk_of(it, kv0, keep);
+    chunk_of(it, kv0, keep, pat);
     if (it + 1 < total) {
       int kv1;
       next_chunk_of(it, kv1);
@@ -209,6 +220,12 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
             const int key = kbase + 8 * (r >> 2) + 4 * half + (r & 3);
             if (key > qpos) s[r] = 0.f;
           }
+        }
+        if (CH == 32 && pat != 0xF) {  // 16-token blocks: drop the blocks my mask row does not keep
+          const int mine = pat >> (2 * (l32 >> 4));
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (!((mine >> (r >> 3)) & 1)) s[r] = 0.f;  // registers 0..7: block 0, 8..15: block 1
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] *= dp[r] - delta_l;
@@ -268,7 +285,11 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
   const int b = bh / p.heads, h = bh - b * p.heads;
   const int tile = DENSE ? rank : p.kv_tiles.order[h * T + rank];  // dense: first key tiles are longest
   const int S = DENSE ? kChunk : p.block_size;
-  const int cpb = S / CH;  // a power of two: / and % below are a shift and a mask
+  // 16-token blocks: a list entry is a unit of two query blocks (32 rows, one step) and my 32 key
+  // rows are two adjacent mask columns, so a lane's keep pattern is 2 x 2 bits per wavefront
+  const bool fine = !DENSE && CH == 32 && S == 16;
+  const int Sg = fine ? 32 : S;  // tokens per list entry
+  const int cpb = Sg / CH;  // a power of two: / and % below are a shift and a mask
   const int cpb_sh = __builtin_ctz(cpb), cpb_m = cpb - 1;
   const int N = p.seqlen;
 
@@ -279,7 +300,7 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
     kvw0 = tile * kBwdBN + wave * 32;
     wave_active = kvw0 < N;
   } else {
-    my_member = (wave * 32) / S;
+    my_member = (wave * 32) / S;  // with 16-token blocks the first of my two (adjacent) columns
     const int blk = p.kv_tiles.members[(h * T + tile) * p.kv_tiles.group + my_member];
     wave_active = blk >= 0;
     kvw0 = blk * S + (wave * 32) % S;
@@ -303,14 +324,21 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
   EntryList list;
   if (!DENSE) list.init(p.kv_tiles.ent + ent_lo, n_ent, lane);
   // chunk `it` of the tile's list: its first row, and whether my mask row / column keeps it
-  auto chunk_of = [&](int it, int& q0, bool& keep) {
+  // `pat` (16-token blocks only): bit 2m + c set when query block c of the unit keeps my column m
+  auto chunk_of = [&](int it, int& q0, bool& keep, int& pat) {
+    pat = 0xF;
     if (DENSE) {
       q0 = N - CH - it * CH;  // from the last query chunk down, like the sparse lists
       keep = true;
     } else {
       const int e = list.get((it >> cpb_sh), lane);
-      q0 = (e >> 8) * S + (cpb - 1 - (it & cpb_m)) * CH;
-      keep = (e >> my_member) & 1;
+      q0 = (e >> 16) * Sg + (cpb - 1 - (it & cpb_m)) * CH;
+      if (fine) {
+        pat = (e >> (4 * wave)) & 0xF;
+        keep = pat != 0;
+      } else {
+        keep = (e >> my_member) & 1;
+      }
     }
   };
   // first row of chunk it+1, right after chunk_of(it)
@@ -319,7 +347,7 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
       q0_n = N - CH - (it + 1) * CH;
     } else {
       const int e = ((it + 1) >> cpb_sh) == (it >> cpb_sh) ? list.get((it >> cpb_sh), lane) : list.peek_next((it >> cpb_sh));
-      q0_n = (e >> 8) * S + (cpb - 1 - ((it + 1) & cpb_m)) * CH;
+      q0_n = (e >> 16) * Sg + (cpb - 1 - ((it + 1) & cpb_m)) * CH;
     }
   };
 
@@ -339,9 +367,9 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
       dma16(delta_b + q0, 16 * ln + (ln < NL ? 0u : stats_gap - 16u * NL), lds_addr(&sm.rs[buf]));
   };
   if (total > 0) {
-    int q0;
+    int q0, pat;
     bool keep;
-    chunk_of(0, q0, keep);
+    chunk_of(0, q0, keep, pat);
     issue_chunk(q0, 0, lane);
   }
 
@@ -373,9 +401,9 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
     const int buf = it & 1;
     int ln = lane;
     asm volatile("" : "+v"(ln));
-    int q0;
+    int q0, pat;
     bool keep;
-    chunk_of(it, q0, keep);
+    chunk_of(it, q0, keep, pat);
     if (it + 1 < total) {
       int q1;
       next_chunk_of(it, q1);
@@ -388,6 +416,7 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
       const int l32 = ln & 31, half = ln >> 5;
       const int trb = Tile::tr_base(ln);
       const int key = kvw0 + l32;
+      const int mine = pat >> (2 * (l32 >> 4));  // 16-token blocks: bit c = query block c keeps my key
 #pragma unroll
       for (int qt = 0; qt < QT; ++qt) {
         const int qbase = q0 + 32 * qt;
@@ -408,6 +437,7 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
             const int r = 4 * g + e;
             float pr = fast_exp2(__builtin_fmaf(s[r], c, -l4[e]));
             if (diag && key > q0 + r0 + e) pr = 0.f;
+            if (CH == 32 && !((mine >> (g >> 1)) & 1)) pr = 0.f;  // query rows 0..15: block 0, 16..31: block 1
             s[r] = pr;
             dp[r] = pr * (dp[r] - d4[e]);
           }
@@ -494,7 +524,7 @@ hipError_t launch_one(const AttnParams& p, int stages, hipStream_t stream) {
 
 hipError_t launch_bwd(const AttnParams& p, bool dense, int stages, hipStream_t stream) {
   // 32-token mask blocks are walked in steps of 32 rows, everything else in steps of 64
-  if (!dense && p.block_size == 32)
+  if (!dense && p.block_size <= 32)
     return p.head_dim == 128 ? launch_one<128, false, 32>(p, stages, stream) : launch_one<64, false, 32>(p, stages, stream);
   if (p.head_dim == 128)
     return dense ? launch_one<128, true, kChunk>(p, stages, stream) : launch_one<128, false, kChunk>(p, stages, stream);

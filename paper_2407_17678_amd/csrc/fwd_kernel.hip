@@ -50,14 +50,18 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
   const bool whole = p.q_row0 == 0 && T_run == T;
   const int tile = (DENSE || !whole) ? p.q_row0 / BM + (T_run - 1 - rank) : p.fwd_tiles.order[h * T + rank];
   const int S = DENSE ? kChunk : p.block_size;
-  const int cpb = S / CH;  // steps per mask block: a power of two, so / and % below are a shift and a mask
+  // 16-token blocks: a list entry is a unit of two blocks (32 keys, one step) and my 32 query rows
+  // are two mask rows, so which keys a lane may see is a 2 x 2 pattern of bits per wavefront
+  const bool fine = !DENSE && CH == 32 && S == 16;
+  const int Sg = fine ? 32 : S;  // tokens per list entry
+  const int cpb = Sg / CH;  // steps per entry: a power of two, so / and % below are a shift and a mask
   const int cpb_sh = __builtin_ctz(cpb), cpb_m = cpb - 1;
 
   const int N = p.seqlen;
   const int qw0 = tile * BM + wave * MW;  // first query row of this wavefront (sequence position)
   const int ql0 = qw0 - p.q_row0;         // the same as a row of q / o / lse
   const bool wave_active = ql0 < p.q_rows;
-  const int my_member = (qw0 / S) - tile * (BM / S);  // which mask row of the tile I am in
+  const int my_member = (qw0 / Sg) - tile * (BM / Sg);  // which mask row of the tile I am in
 
   const uint16_t* qb = p.q + b * p.q_sb + h * p.q_sh;
   const uint16_t* kb = p.k + b * p.kv_sb + h * p.kv_sh;
@@ -85,14 +89,21 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
   EntryList list;
   if (!DENSE) list.init(p.fwd_tiles.ent + ent_lo, n_ent, lane);
   // step `it` of the tile's list: its first key row, and whether my mask row keeps the block
-  auto chunk_of = [&](int it, int& kv0, bool& keep) {
+  // `pat` (16-token blocks only): bit 2m + c set when mask row m of my two keeps block c of the unit
+  auto chunk_of = [&](int it, int& kv0, bool& keep, int& pat) {
+    pat = 0xF;
     if (DENSE) {
       kv0 = it * CH;
       keep = true;
     } else {
       const int e = list.get((it >> cpb_sh), lane);
-      kv0 = (e >> 8) * S + ((it & cpb_m)) * CH;
-      keep = (e >> my_member) & 1;
+      kv0 = (e >> 16) * Sg + ((it & cpb_m)) * CH;
+      if (fine) {
+        pat = (e >> (4 * wave)) & 0xF;
+        keep = pat != 0;
+      } else {
+        keep = (e >> my_member) & 1;
+      }
     }
   };
   // first key row of step it+1, right after chunk_of(it)
@@ -101,7 +112,7 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
       kv0_n = (it + 1) * CH;
     } else {
       const int e = ((it + 1) >> cpb_sh) == (it >> cpb_sh) ? list.get((it >> cpb_sh), lane) : list.peek_next((it >> cpb_sh));
-      kv0_n = (e >> 8) * S + (((it + 1) & cpb_m)) * CH;
+      kv0_n = (e >> 16) * Sg + (((it + 1) & cpb_m)) * CH;
     }
   };
 
@@ -116,9 +127,9 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
   const int trb = Tile::tr_base(lane);
   constexpr int PW = Tile::kPerWave;
   if (total > 0) {
-    int kv0;
+    int kv0, pat;
     bool keep;
-    chunk_of(0, kv0, keep);
+    chunk_of(0, kv0, keep, pat);
     Tile::issue(plan, kb + (int64_t)kv0 * p.kv_st, sk[0], wave);
     Tile::issue(plan, vb + (int64_t)kv0 * p.kv_st, sv[0], wave);
   }
@@ -130,9 +141,9 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
     const uint16_t* vs = sv[it & 1];
     const uint16_t* kn = sk[(it & 1) ^ 1];
     const uint16_t* vn = sv[(it & 1) ^ 1];
-    int kv0;
+    int kv0, pat;
     bool keep;
-    chunk_of(it, kv0, keep);
+    chunk_of(it, kv0, keep, pat);
     // The next step's direct loads are spread between the MFMAs of the first contraction, or
     // issued at once by a wavefront that has nothing to compute in this step.  The last step
     // loads its own chunk once more into the idle stage: nothing reads it, and the loop body
@@ -168,6 +179,12 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
           if (n >= PW && n < 2 * PW) Tile::issue_one(plan, n - PW, vg, vn, wave);
         }
       static_assert(2 * PW <= KT * (D / 16), "every load has an MFMA to follow");
+      if (CH == 32 && pat != 0xF) {  // 16-token blocks: drop the blocks my mask row does not keep
+        const int mine = pat >> (2 * (l32 >> 4));
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (!((mine >> (r >> 3)) & 1)) s[0][r] = kNegInf;  // registers 0..7: block 0, 8..15: block 1
+      }
       if (kv0 + CH - 1 > qw0) {  // diagonal: key position must not exceed query position
         const int qpos = qw0 + l32;
 #pragma unroll
@@ -241,7 +258,7 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
 template <int D, bool DENSE>
 hipError_t launch_one(const AttnParams& p, hipStream_t stream) {
   const int grid = grid_for(p.batch * p.heads, (p.q_rows + kFwdBM - 1) / kFwdBM);
-  if (!DENSE && p.block_size == 32)  // 32-token mask blocks: steps of 32 keys
+  if (!DENSE && p.block_size <= 32)  // 16- and 32-token mask blocks: steps of 32 keys
     hipLaunchKernelGGL((fwd_kernel<D, false, 32>), dim3(grid), dim3(kThreads), 0, stream, p);
   else
     hipLaunchKernelGGL((fwd_kernel<D, DENSE, kFwdChunk>), dim3(grid), dim3(kThreads), 0, stream, p);

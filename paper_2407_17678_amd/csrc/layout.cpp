@@ -85,12 +85,15 @@ int64_t row_blocks(const s2_layout_params& p, int head, int i, int32_t* out, int
 
 int build_host(const s2_layout_params& p, s2_layout& L) {
   if (p.num_heads < 1 || p.num_blocks < 1 || p.head_index_base < 0) return S2_ERR_BAD_PARAM;
-  if (p.block_size != 32 && p.block_size != 64 && p.block_size != 128) return S2_ERR_BAD_PARAM;
+  if (p.block_size != 16 && p.block_size != 32 && p.block_size != 64 && p.block_size != 128)
+    return S2_ERR_BAD_PARAM;
+  if (p.block_size == 16 && (p.num_blocks & 1)) return S2_ERR_BAD_PARAM;  // whole 32-token units
   if (!p.dense && (p.local_blocks < 1 || p.stride < 0 || p.window_blocks < 0)) return S2_ERR_BAD_PARAM;
   if (p.dense != 0 && p.dense != 1) return S2_ERR_BAD_PARAM;
   const int H = p.num_heads, B = p.num_blocks;
   if ((int64_t)H * B + 1 > std::numeric_limits<int32_t>::max()) return S2_ERR_OVERFLOW;
   if ((int64_t)B * p.block_size > std::numeric_limits<int32_t>::max()) return S2_ERR_OVERFLOW;
+  if (B / (p.block_size < 32 ? 2 : 1) > kMaxListUnits) return S2_ERR_OVERFLOW;
 
   L.p = p;
   // pass 1: count
@@ -139,10 +142,12 @@ int build_host(const s2_layout_params& p, s2_layout& L) {
 int build_from_csr(int num_heads, int num_blocks, int block_size, const int32_t* row_ptr,
                    const int32_t* col_idx, s2_layout& L) {
   if (num_heads < 1 || num_blocks < 1) return S2_ERR_BAD_PARAM;
-  if (block_size != 32 && block_size != 64 && block_size != 128) return S2_ERR_BAD_PARAM;
+  if (block_size != 16 && block_size != 32 && block_size != 64 && block_size != 128) return S2_ERR_BAD_PARAM;
+  if (block_size == 16 && (num_blocks & 1)) return S2_ERR_BAD_PARAM;  // whole 32-token units
   const int H = num_heads, B = num_blocks;
   if ((int64_t)H * B + 1 > std::numeric_limits<int32_t>::max()) return S2_ERR_OVERFLOW;
   if ((int64_t)B * block_size > std::numeric_limits<int32_t>::max()) return S2_ERR_OVERFLOW;
+  if (B / (block_size < 32 ? 2 : 1) > kMaxListUnits) return S2_ERR_OVERFLOW;
   const size_t rows = (size_t)H * B;
   if (row_ptr[0] != 0) return S2_ERR_BAD_PARAM;
   int max_row = 0;
@@ -187,6 +192,9 @@ int build_from_csr(int num_heads, int num_blocks, int block_size, const int32_t*
 }
 
 void build_tiles(const s2_layout& L, int group, bool transpose, TileList& out) {
+  // partner blocks per entry: the kernels walk partners in units of at least 32 tokens, so with
+  // 16-token blocks an entry covers two of them
+  const int sub = L.p.block_size < 32 ? 32 / L.p.block_size : 1;
   const int H = L.p.num_heads, B = L.p.num_blocks;
   const std::vector<int32_t>& ptr = transpose ? L.col_ptr : L.row_ptr;
   const std::vector<int32_t>& idx = transpose ? L.row_idx : L.col_idx;
@@ -205,7 +213,8 @@ void build_tiles(const s2_layout& L, int group, bool transpose, TileList& out) {
     // which blocks go together: rows stay in order; columns are sorted by how many rows keep
     // them (longest first, ties by index) so that stripe columns pair up with stripe columns
     std::iota(seq.begin(), seq.end(), 0);
-    if (transpose && group > 1)
+    // (with 16-token blocks members stay adjacent, which the kernel relies on for its key rows)
+    if (transpose && group > 1 && sub == 1)
       std::stable_sort(seq.begin(), seq.end(),
                        [&](int a, int b) { return hp0[a + 1] - hp0[a] > hp0[b + 1] - hp0[b]; });
     for (int t = 0; t < T; ++t) {
@@ -221,12 +230,15 @@ void build_tiles(const s2_layout& L, int group, bool transpose, TileList& out) {
       for (;;) {  // k-way merge of ascending lists
         int best = std::numeric_limits<int>::max();
         for (int r = 0; r < n_members; ++r)
-          if (cur[r] < end[r]) best = std::min(best, (int)idx[cur[r]]);
+          if (cur[r] < end[r]) best = std::min(best, (int)idx[cur[r]] / sub);
         if (best == std::numeric_limits<int>::max()) break;
         int bits = 0;
         for (int r = 0; r < n_members; ++r)
-          if (cur[r] < end[r] && idx[cur[r]] == best) { bits |= 1 << r; ++cur[r]; }
-        out.ent.push_back((int32_t)((best << 8) | bits));
+          while (cur[r] < end[r] && idx[cur[r]] / sub == best) {
+            bits |= 1 << (r * sub + idx[cur[r]] % sub);
+            ++cur[r];
+          }
+        out.ent.push_back((int32_t)((best << 16) | bits));
       }
       // Column tiles are walked from the last query block down.  Every stripe tile of a head ends
       // at the last row, so tiles started together then read the same Q / dO blocks at the same

@@ -8,14 +8,19 @@
 namespace s2 {
 
 // Merged tile list: groups of `group` block rows (or block columns) share one list of partner
-// blocks; each entry packs (partner_index << 8) | membership_bits, bit r set when member r of
-// the group keeps that partner.  This is the Merge-Q idea of section 3.2 (one large tile serves
+// blocks; each entry packs (partner_index << 16) | membership_bits, bit r set when member r of
+// the group keeps that partner.  With 16-token blocks a partner is a UNIT of two adjacent blocks
+// (the kernels step through partners 32 tokens at a time at least) and bit 2r + c says that
+// member r keeps block c of the unit.  This is the Merge-Q idea of section 3.2 (one large tile serves
 // several fine-grained mask rows) and its mirror image for key tiles.  Row groups are
 // consecutive rows.  Column groups are formed from columns with similar partner sets (a stripe
 // column is attended by every later row, its neighbours only by the local window), so members
-// of a column group need not be adjacent: `members` names them.
+// of a column group need not be adjacent: `members` names them (they are adjacent for 16-token
+// blocks, where a wavefront's 32 key rows span two members).
+constexpr int kMaxListUnits = 1 << 15;  // partner indices take the 15 bits above the membership bits
+
 struct TileList {
-  int group = 0;                 // members per tile (1..8)
+  int group = 0;                 // members per tile (1..8; members x blocks per unit <= 16 bits)
   int tiles_per_head = 0;        // ceil(B / group)
   std::vector<int32_t> ptr;      // [H*tiles_per_head + 1]
   std::vector<int32_t> ent;      // packed entries; partner ascending inside a row tile,

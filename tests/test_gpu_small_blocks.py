@@ -1,6 +1,6 @@
-"""GPU parity with 32-token mask blocks (section 3.2: fine-grained shards inside a large query
-tile): forward, backward, decode, paged decode and a caller-supplied pattern, all against the fp64
-oracle run with the same block size."""
+"""GPU parity with 32- and 16-token mask blocks (section 3.2: fine-grained shards inside a large
+query tile): forward, backward, decode, paged decode and a caller-supplied pattern, all against the
+fp64 oracle run with the same block size."""
 
 import dataclasses
 
@@ -18,51 +18,57 @@ pytestmark = pytest.mark.gpu
 LSE_TOL, GRAD_TOL = 1e-3, 2e-2
 
 
-def _w32(name, local_blocks, stride):
-    return dataclasses.replace(synth.WORKLOADS[name], block_size=32, local_blocks=local_blocks, stride=stride)
+def _small(name, S, local_blocks, stride):
+    return dataclasses.replace(synth.WORKLOADS[name], block_size=S, local_blocks=local_blocks, stride=stride)
 
 
+@pytest.mark.parametrize("S", [32, 16])
 @pytest.mark.parametrize("name,heads,batch,seqlen,B_l,s", [
     ("1p3b_8k", 4, 2, 1024, 4, 8),     # D=128
     ("7b_32k", 3, 1, 2048, 9, 16),     # longer rows, more stripes than heads
     ("tiny", 4, 1, 640, 3, 4),         # D=64, five 128-row tiles
     ("1p3b_8k", 2, 1, 128, 1, 0),      # one tile, diagonal blocks only
+    ("1p3b_8k", 5, 1, 768, 1, 3),      # odd stride: stripes fall on either block of a 32-token unit
+    ("tiny", 3, 1, 512, 2, 5),
 ])
-def test_block32_fwd_bwd(name, heads, batch, seqlen, B_l, s):
-    w = _w32(name, B_l, s)
+def test_small_blocks_fwd_bwd(name, heads, batch, seqlen, B_l, s, S):
+    w = _small(name, S, B_l, s)
     qb, kb, vb, gb = synth.train_inputs(w, heads=heads, batch=batch, seqlen=seqlen)
-    print("block-32 case", name, qb.shape, "B_l", B_l, "stride", s, flush=True)
+    print("small-block case", name, qb.shape, "S", S, "B_l", B_l, "stride", s, flush=True)
     out = G.run_fwd_bwd(w, qb, kb, vb, gb)
     M = G.oracle_mask(w, heads, seqlen)
-    assert M.shape[1] == seqlen // 32
+    assert M.shape[1] == seqlen // S
     dQ, dK, dV, O, LSE = orc.attention_backward(G.bits_f64(qb), G.bits_f64(kb), G.bits_f64(vb), G.bits_f64(gb),
-                                                M, 32, w.scale)
+                                                M, S, w.scale)
     assert G.o_excess(G.to_f64(out["o"]), O) <= 0
     assert np.abs(G.to_f64(out["lse"]) - LSE).max() <= LSE_TOL
     for n, ref in (("dq", dQ), ("dk", dK), ("dv", dV)):
         assert G.rel_l2(G.to_f64(out[n]), ref) <= GRAD_TOL, n
 
 
-def test_block32_zero_queries_count_keys():
+@pytest.mark.parametrize("S,B_l,s", [(32, 2, 4), (16, 2, 4), (16, 1, 3), (16, 3, 7)])
+def test_small_blocks_zero_queries_count_keys(S, B_l, s):
     # Q = 0: LSE = ln(#kept keys), which checks every row's kept set through the kernel
-    w = _w32("tiny", 2, 4)
+    w = _small("tiny", S, B_l, s)
     H, N = 4, 512
     qb, kb, vb, _ = synth.train_inputs(w, heads=H, batch=1, seqlen=N)
     qb = np.zeros_like(qb)
     o, lse, lay, _ = G.run_fwd(w, qb, kb, vb)
     M = G.oracle_mask(w, H, N)
     t = np.arange(N)
-    want = np.log(32.0 * (M[:, t // 32].sum(axis=2) - 1) + (t % 32) + 1)
+    want = np.log(float(S) * (M[:, t // S].sum(axis=2) - 1) + (t % S) + 1)
     assert np.abs(G.to_f64(lse)[0] - want).max() <= 1e-5
 
 
-def test_block32_custom_pattern():
+@pytest.mark.parametrize("S,Bk,density", [(32, 24, 0.35), (16, 48, 0.35), (16, 40, 0.08), (16, 24, 0.9)])
+def test_small_blocks_custom_pattern(S, Bk, density):
+    # random rows: with 16-token blocks every 2 x 2 keep pattern of a (query pair, key pair) occurs
     rng = np.random.default_rng(8)
-    H, Bk, S = 3, 24, 32
-    M = np.tril(rng.random((H, Bk, Bk)) < 0.35)
+    H = 3
+    M = np.tril(rng.random((H, Bk, Bk)) < density)
     i = np.arange(Bk)
     M[:, i, i] = True
-    w = _w32("1p3b_8k", 1, 0)
+    w = _small("1p3b_8k", S, 1, 0)
     N = Bk * S
     qb, kb, vb, gb = synth.train_inputs(w, heads=H, batch=1, seqlen=N)
     row_ptr, col_idx, _, _ = orc.compressed_layout(M)
@@ -83,11 +89,12 @@ def test_block32_custom_pattern():
         assert G.rel_l2(G.to_f64(got), ref) <= GRAD_TOL, n
 
 
+@pytest.mark.parametrize("S", [32, 16])
 @pytest.mark.parametrize("paged", [False, True])
-def test_block32_decode(paged):
-    w = _w32("7b_decode", 5, 8)
-    S, heads, max_len = 32, 6, 1000
-    lens = np.array([1, 31, 32, 33, 1000, 777], dtype=np.int32)
+def test_small_blocks_decode(paged, S):
+    w = _small("7b_decode", S, 5, 8)
+    heads, max_len = 6, 1000
+    lens = np.array([1, 15, 16, 17, 31, 32, 33, 1000, 777], dtype=np.int32)
     nseq = len(lens)
     qb, kcb, vcb, lens = synth.decode_inputs_small(w, nseq, heads, max_len, lengths=lens)
     params = B.layout_params(heads, 1, S, w.local_blocks, w.stride, 0, w.window_blocks, 0)
@@ -127,7 +134,8 @@ def test_block32_decode(paged):
             assert abs(float(lse[b, h]) - ref_lse) <= LSE_TOL, (b, h)
 
 
-@pytest.mark.parametrize("S,seqlen", [(64, 576), (64, 64), (32, 160), (32, 32), (32, 96)])
+@pytest.mark.parametrize("S,seqlen", [(64, 576), (64, 64), (32, 160), (32, 32), (32, 96), (16, 160), (16, 32),
+                                      (16, 96)])
 def test_sequences_that_end_inside_a_128_row_tile(S, seqlen):
     # the last tile of queries (and of keys) is partly empty: wavefronts beyond the sequence idle
     w = dataclasses.replace(synth.WORKLOADS["1p3b_8k"], block_size=S, local_blocks=2, stride=3)

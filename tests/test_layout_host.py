@@ -74,10 +74,13 @@ def test_layout_variants():
     assert _compare(16, 128, 64, 2, 18)["covers_all"] == 0
     _compare(4, 33, 128, 200, 3)        # B_l >= B is dense
     _compare(8, 64, 64, 4, 8, base=8)   # second tensor-parallel shard of 16 heads
+    _compare(6, 96, 16, 3, 5)           # 16-token blocks
+    _compare(6, 96, 32, 3, 5)
 
 
 @pytest.mark.parametrize("kw,code", [
-    (dict(num_heads=0), -2), (dict(num_blocks=0), -2), (dict(block_size=16), -2), (dict(block_size=96), -2),
+    (dict(num_heads=0), -2), (dict(num_blocks=0), -2), (dict(block_size=8), -2), (dict(block_size=96), -2),
+    (dict(block_size=16, num_blocks=5), -2),   # 16-token blocks come in pairs
     (dict(local_blocks=0), -2), (dict(stride=-1), -2), (dict(window_blocks=-1), -2),
     (dict(head_index_base=-1), -2), (dict(dense=2), -2),
 ])
@@ -207,7 +210,7 @@ def test_resident_blocks_errors():
     assert lib.s2_kv_resident_blocks(C.byref(p), 4, 10, buf, 2, C.byref(n)) == -2   # head out of range
     assert lib.s2_kv_resident_blocks(C.byref(p), -1, 10, buf, 2, C.byref(n)) == -2
     assert lib.s2_kv_resident_blocks(C.byref(p), 0, 0, buf, 2, C.byref(n)) == -2    # length < 1
-    bad = B.layout_params(4, 1, 16, 2, 4)
+    bad = B.layout_params(4, 1, 8, 2, 4)
     assert lib.s2_kv_resident_blocks(C.byref(bad), 0, 10, buf, 2, C.byref(n)) == -2
     # capacity too small: count still reported, first entries written
     assert lib.s2_kv_resident_blocks(C.byref(p), 0, 64 * 8, buf, 2, C.byref(n)) == -8
