@@ -29,6 +29,8 @@ What each function follows:
 * ``resident_blocks`` / ``paged_decode_row`` - section 4.1's KV-efficient
   cache: which blocks some later query can still attend (the rest may be
   evicted), and decoding against a cache stored as pages behind a block table.
+* ``decode_row_mask`` / ``resident_blocks_mask`` / ``paged_decode_row_mask`` -
+  the same three for a caller-supplied block mask instead of section 4.2's rule.
 
 Readings taken where the paper is silent (each is also listed in the design
 notes): the local case is restricted to j <= i (causal); the head offset is
@@ -419,3 +421,43 @@ def paged_decode_row(q, k_pages, v_pages, table_row, length, global_head, block_
             v[j * block_size:(j + 1) * block_size] = 0.0
     return decode_row(q, k, v, L, global_head, block_size, local_blocks, stride, scale,
                       window_blocks, dense)
+
+
+# ---------------------------------------------------------------------------------------------
+# Decode and eviction under a caller-supplied block mask (section 4.1 applied to any pattern)
+# ---------------------------------------------------------------------------------------------
+def decode_row_mask(q, k_cache, v_cache, length, Mh, block_size, scale):
+    """One decoding step of one head whose pattern is the block mask Mh [B,B].
+
+    The newest token, at position L-1, is query row L-1 of the causal attention
+    that Mh describes: the result is that row of the forward, by definition.
+    q [D]; k_cache, v_cache [>=L, D].  Returns (o [D], lse).
+    """
+    L = int(length)
+    o, lse = forward_rows(_f64(q)[None, :], [L - 1], k_cache[:L], v_cache[:L], Mh, block_size, scale)
+    return o[0], lse[0]
+
+
+def resident_blocks_mask(Mh, length, block_size):
+    """Blocks that must stay cached once `length` tokens are cached, for a mask Mh [B,B].
+
+    Section 4.1's rule as a definition: block j among those that exist stays iff
+    the row of the newest token or any later row of Mh keeps it.
+    """
+    L = int(length)
+    i = (L - 1) // block_size
+    return [j for j in range(i + 1) if bool(Mh[i:, j].any())]
+
+
+def paged_decode_row_mask(q, k_pages, v_pages, table_row, length, Mh, block_size, scale):
+    """decode_row_mask on the logical cache that the page table describes (see paged_decode_row)."""
+    L = int(length)
+    B = -(-L // block_size)
+    k = gather_pages(k_pages, table_row, B, block_size)
+    v = gather_pages(v_pages, table_row, B, block_size)
+    i = (L - 1) // block_size
+    for j in range(B):
+        if not Mh[i, j]:  # dropped by the mask: never looked at, so absent (NaN) rows must not reach 0 * NaN
+            k[j * block_size:(j + 1) * block_size] = 0.0
+            v[j * block_size:(j + 1) * block_size] = 0.0
+    return decode_row_mask(q, k, v, L, Mh, block_size, scale)

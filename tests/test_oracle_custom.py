@@ -98,3 +98,86 @@ def test_arbitrary_mask_against_loops_and_finite_differences():
             args_p[which] = ap; args_m[which] = am
             fd = (loss(*args_p) - loss(*args_m)) / (2 * eps)
             assert abs(fd - grad[idx]) < 1e-6 * max(1.0, abs(fd))
+
+
+# ---- decode and eviction under an arbitrary mask -------------------------------------------------
+
+def test_decode_row_mask_agrees_with_the_closed_form_decode_on_the_hhst_mask():
+    # decode_row evaluates section 4.2's predicate token by token; decode_row_mask takes a row of
+    # the forward under the materialised mask: two routes to the same definition
+    rng = np.random.default_rng(5)
+    H, B, S, D, B_l, s = 3, 9, 4, 6, 2, 3
+    M = O.block_mask(H, B, B_l, s)
+    k = rng.standard_normal((B * S, D))
+    v = rng.standard_normal((B * S, D))
+    q = rng.standard_normal(D)
+    for h in range(H):
+        for L in (1, 4, 5, 17, 35, 36):
+            a, la = O.decode_row_mask(q, k, v, L, M[h], S, 0.4)
+            b, lb = O.decode_row(q, k, v, L, h, S, B_l, s, 0.4)
+            assert np.allclose(a, b, rtol=0, atol=1e-13) and abs(la - lb) < 1e-13
+
+
+def test_decode_row_mask_zero_query_counts_keys():
+    rng = np.random.default_rng(6)
+    B, S, D = 6, 4, 3
+    Mh = random_mask(rng, 1, B, 0.5)[0]
+    v = rng.standard_normal((B * S, D))
+    k = rng.standard_normal((B * S, D))
+    for L in (1, 3, 4, 9, 24):
+        i = (L - 1) // S
+        toks = [u for u in range(L) if Mh[i, u // S]]
+        o, lse = O.decode_row_mask(np.zeros(D), k, v, L, Mh, S, 1.0)
+        assert abs(lse - np.log(len(toks))) < 1e-13
+        assert np.allclose(o, v[toks].mean(axis=0), atol=1e-13)
+
+
+def test_resident_blocks_mask_by_hand():
+    # rows: 0:{0} 1:{0,1} 2:{2} 3:{0,3}.  Row 2 does not read block 0, yet row 3 will: it stays
+    # (a pattern that is not KV-efficient in section 4.1's sense pays with blocks held but unread)
+    Mh = np.zeros((4, 4), dtype=bool)
+    for i, cols in enumerate([[0], [0, 1], [2], [0, 3]]):
+        Mh[i, cols] = True
+    S = 4
+    assert O.resident_blocks_mask(Mh, 1, S) == [0]
+    assert O.resident_blocks_mask(Mh, 4, S) == [0]
+    assert O.resident_blocks_mask(Mh, 5, S) == [0, 1]
+    assert O.resident_blocks_mask(Mh, 9, S) == [0, 2]
+    assert O.resident_blocks_mask(Mh, 12, S) == [0, 2]
+    assert O.resident_blocks_mask(Mh, 13, S) == [0, 3]
+
+
+def test_resident_blocks_mask_agrees_with_closed_form_far_from_the_end():
+    # with enough later rows in the mask, scanning it equals the closed-form scan of the rule
+    H, B, S, B_l, s = 4, 40, 8, 3, 5
+    M = O.block_mask(H, B, B_l, s)
+    for h in range(H):
+        for L in (1, 8, 9, 63, 64, 100, 160):
+            assert O.resident_blocks_mask(M[h], L, S) == O.resident_blocks(L, h, S, B_l, s)
+
+
+def test_paged_decode_row_mask_ignores_absent_dropped_blocks_and_flags_absent_kept_ones():
+    rng = np.random.default_rng(7)
+    B, S, D = 6, 4, 5
+    Mh = random_mask(rng, 1, B, 0.4)[0]
+    L = 22
+    i = (L - 1) // S
+    kc = rng.standard_normal((B * S, D))
+    vc = rng.standard_normal((B * S, D))
+    q = rng.standard_normal(D)
+    want, want_lse = O.decode_row_mask(q, kc, vc, L, Mh, S, 0.7)
+    kept = [j for j in range(i + 1) if Mh[i, j]]
+    table = -np.ones(B, dtype=np.int32)
+    perm = rng.permutation(len(kept) + 2)
+    for n, j in enumerate(kept):
+        table[j] = perm[n]
+    kp = rng.standard_normal((len(kept) + 2, S, D))
+    vp = rng.standard_normal((len(kept) + 2, S, D))
+    for j in kept:
+        kp[table[j]] = kc[j * S:(j + 1) * S]
+        vp[table[j]] = vc[j * S:(j + 1) * S]
+    got, got_lse = O.paged_decode_row_mask(q, kp, vp, table, L, Mh, S, 0.7)
+    assert np.allclose(got, want, atol=1e-13) and abs(got_lse - want_lse) < 1e-13
+    table[kept[0]] = -1
+    got, _ = O.paged_decode_row_mask(q, kp, vp, table, L, Mh, S, 0.7)
+    assert np.isnan(got).all()
