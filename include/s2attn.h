@@ -150,7 +150,7 @@ int s2_layout_build(const s2_layout_params* params, s2_layout** out);
  * ordered head-major, and inside a row the kept KV block columns strictly ascending, none above
  * the row's own index (causal) and the row's own index last (a token always attends its own
  * block, so no softmax is empty).  The arrays are copied.  The result works with s2_attn_fwd /
- * s2_attn_bwd; decode takes its pattern from s2_layout_params and has no such variant.
+ * s2_attn_bwd, and with s2_attn_decode_layout / s2_attn_decode_paged_layout.
  * Errors: NULL, BAD_PARAM (H<1, B<1, S not 16/32/64/128, S = 16 with odd B, or a row breaking the rules above), OVERFLOW,
  * HIP. */
 int s2_layout_from_csr(int32_t num_heads, int32_t num_blocks, int32_t block_size,
@@ -235,6 +235,23 @@ int s2_attn_decode_paged(const s2_layout_params* p, const s2_paged_decode_args* 
  * OVERFLOW when capacity is too small (count is still set). */
 int s2_kv_resident_blocks(const s2_layout_params* p, int32_t head, int32_t length,
                           int32_t* blocks, int32_t capacity, int32_t* count);
+
+/* The three calls above for a layout handle instead of the closed form, so that a pattern given
+ * to s2_layout_from_csr (section 3: per head, per context range) also decodes: the token at
+ * position L-1 attends the blocks that row (L-1) div S of the layout keeps.  The layout must
+ * cover the cache (max_len, or max_blocks * S, at most B*S) and live on the current device.
+ * s2_layout_resident_blocks scans the layout's later rows: with a pattern that does not follow
+ * section 4.1's rule a block can be resident without being read at this step.  It also accepts
+ * layouts from s2_layout_build, where it agrees with s2_kv_resident_blocks as long as the
+ * layout has rows beyond the stripe and window reach of the current one.
+ * Errors: as the calls above, plus SHAPE (cache longer than the layout), NO_DEVICE; for
+ * s2_layout_resident_blocks BAD_PARAM also when length > B*S. */
+int s2_attn_decode_layout(const s2_layout* layout, const s2_decode_args* a, float scale,
+                          void* workspace, size_t workspace_bytes, void* stream);
+int s2_attn_decode_paged_layout(const s2_layout* layout, const s2_paged_decode_args* a, float scale,
+                                void* workspace, size_t workspace_bytes, void* stream);
+int s2_layout_resident_blocks(const s2_layout* layout, int32_t head, int32_t length,
+                              int32_t* blocks, int32_t capacity, int32_t* count);
 
 /* ---- diagnostics -------------------------------------------------------------------------- */
 

@@ -76,7 +76,8 @@ EXPORTS = (
     "s2_layout_build", "s2_layout_from_csr", "s2_layout_destroy", "s2_layout_get", "s2_attn_fwd", "s2_attn_fwd_rows", "s2_attn_bwd",
     "s2_attn_bwd_workspace_bytes", "s2_attn_bwd_stages", "s2_dense_causal_fwd", "s2_dense_causal_bwd", "s2_attn_decode",
     "s2_attn_decode_workspace_bytes", "s2_attn_decode_default_splits", "s2_attn_decode_paged",
-    "s2_kv_resident_blocks", "s2_status_string",
+    "s2_kv_resident_blocks", "s2_attn_decode_layout", "s2_attn_decode_paged_layout",
+    "s2_layout_resident_blocks", "s2_status_string",
     "s2_last_hip_error", "s2_version",
 )
 
@@ -115,6 +116,12 @@ def lib():
                                        C.c_void_p, C.c_size_t, C.c_void_p]
     L.s2_kv_resident_blocks.argtypes = [C.POINTER(LayoutParams), C.c_int32, C.c_int32,
                                         C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_int32)]
+    L.s2_attn_decode_layout.argtypes = [C.c_void_p, C.POINTER(DecodeArgs), C.c_float, C.c_void_p,
+                                        C.c_size_t, C.c_void_p]
+    L.s2_attn_decode_paged_layout.argtypes = [C.c_void_p, C.POINTER(PagedDecodeArgs), C.c_float,
+                                              C.c_void_p, C.c_size_t, C.c_void_p]
+    L.s2_layout_resident_blocks.argtypes = [C.c_void_p, C.c_int32, C.c_int32,
+                                            C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_int32)]
     L.s2_status_string.argtypes = [C.c_int]
     L.s2_status_string.restype = C.c_char_p
     L.s2_last_hip_error.restype = C.c_int
@@ -286,6 +293,20 @@ def s2_attn_decode(params, q, k_cache, v_cache, seq_lens, o, lse, scale, workspa
            "s2_attn_decode")
 
 
+def s2_attn_decode_layout(layout, q, k_cache, v_cache, seq_lens, o, lse, scale, workspace, max_len,
+                          num_splits=0, stream=None):
+    """s2_attn_decode following the rows of a Layout (any pattern) instead of the closed form."""
+    nseq, H, D = q.shape
+    assert q.is_contiguous() and o.is_contiguous() and k_cache.stride() == v_cache.stride()
+    assert k_cache.stride(3) == 1
+    a = DecodeArgs(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seq_lens), _ptr(o), _ptr(lse),
+                   nseq, H, D, max_len, num_splits,
+                   k_cache.stride(0), k_cache.stride(1), k_cache.stride(2))
+    _check(lib().s2_attn_decode_layout(layout.handle, C.byref(a), scale, _ptr(workspace),
+                                       workspace.numel() * workspace.element_size(), _stream_ptr(stream)),
+           "s2_attn_decode_layout")
+
+
 def s2_attn_decode_paged(params, q, k_pages, v_pages, block_table, seq_lens, o, lse, scale, workspace,
                          missing=None, num_splits=0, stream=None):
     """k_pages, v_pages: [num_pages, block_size, head_dim]; block_table: int32 [nseq, heads, max_blocks]."""
@@ -301,6 +322,21 @@ def s2_attn_decode_paged(params, q, k_pages, v_pages, block_table, seq_lens, o, 
            "s2_attn_decode_paged")
 
 
+def s2_attn_decode_paged_layout(layout, q, k_pages, v_pages, block_table, seq_lens, o, lse, scale, workspace,
+                                missing=None, num_splits=0, stream=None):
+    """s2_attn_decode_paged following the rows of a Layout (any pattern) instead of the closed form."""
+    nseq, H, D = q.shape
+    assert q.is_contiguous() and o.is_contiguous() and block_table.is_contiguous()
+    assert k_pages.stride() == v_pages.stride() and k_pages.stride(2) == 1
+    assert tuple(block_table.shape[:2]) == (nseq, H)
+    a = PagedDecodeArgs(_ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(block_table), _ptr(seq_lens), _ptr(o),
+                        _ptr(lse), _ptr(missing), nseq, H, D, block_table.shape[2], k_pages.shape[0],
+                        num_splits, k_pages.stride(0), k_pages.stride(1))
+    _check(lib().s2_attn_decode_paged_layout(layout.handle, C.byref(a), scale, _ptr(workspace),
+                                             workspace.numel() * workspace.element_size(), _stream_ptr(stream)),
+           "s2_attn_decode_paged_layout")
+
+
 def s2_kv_resident_blocks(params, head, length):
     """Ascending list of the logical KV blocks local head `head` still needs with `length` tokens cached."""
     n = C.c_int32(0)
@@ -310,4 +346,16 @@ def s2_kv_resident_blocks(params, head, length):
     buf = (C.c_int32 * max(1, n.value))()
     _check(lib().s2_kv_resident_blocks(C.byref(params), head, length, buf, n.value, C.byref(n)),
            "s2_kv_resident_blocks")
+    return list(buf[:n.value])
+
+
+def s2_layout_resident_blocks(layout, head, length):
+    """The same from the rows of a Layout: blocks that its row (length-1) div S or a later row keeps."""
+    n = C.c_int32(0)
+    st = lib().s2_layout_resident_blocks(layout.handle, head, length, None, 0, C.byref(n))
+    if st not in (0, -8):
+        _check(st, "s2_layout_resident_blocks")
+    buf = (C.c_int32 * max(1, n.value))()
+    _check(lib().s2_layout_resident_blocks(layout.handle, head, length, buf, n.value, C.byref(n)),
+           "s2_layout_resident_blocks")
     return list(buf[:n.value])

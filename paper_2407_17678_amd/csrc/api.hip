@@ -43,6 +43,15 @@ void free_tiles(s2::TileList& t) {
   t.d_ptr = t.d_ent = t.d_order = t.d_members = nullptr;
 }
 
+void free_device_copies(s2_layout* L) {
+  free_tiles(L->fwd_tiles);
+  free_tiles(L->q_tiles);
+  free_tiles(L->kv_tiles);
+  if (L->d_row_ptr) (void)hipFree(L->d_row_ptr);
+  if (L->d_col_idx) (void)hipFree(L->d_col_idx);
+  L->d_row_ptr = L->d_col_idx = nullptr;
+}
+
 s2::DevTiles dev_tiles(const s2::TileList& t) {
   s2::DevTiles d;
   d.ptr = t.d_ptr;
@@ -151,11 +160,10 @@ int finish_layout(s2_layout* L, int st, s2_layout** out) {
   if (hipGetDeviceCount(&ndev) == hipSuccess && ndev > 0) {
     int dev = 0;
     bool ok = hip_ok(hipGetDevice(&dev)) && upload_tiles(L->fwd_tiles) && upload_tiles(L->q_tiles) &&
-              upload_tiles(L->kv_tiles);
+              upload_tiles(L->kv_tiles) && upload(L->row_ptr, &L->d_row_ptr) &&
+              upload(L->col_idx, &L->d_col_idx);
     if (!ok) {
-      free_tiles(L->fwd_tiles);
-      free_tiles(L->q_tiles);
-      free_tiles(L->kv_tiles);
+      free_device_copies(L);
       delete L;
       return S2_ERR_HIP;
     }
@@ -200,11 +208,7 @@ int s2_layout_from_csr(int32_t num_heads, int32_t num_blocks, int32_t block_size
 
 int s2_layout_destroy(s2_layout* layout) {
   if (!layout) return S2_ERR_NULL;
-  if (layout->on_device) {
-    free_tiles(layout->fwd_tiles);
-    free_tiles(layout->q_tiles);
-    free_tiles(layout->kv_tiles);
-  }
+  if (layout->on_device) free_device_copies(layout);
   delete layout;
   return S2_OK;
 }
@@ -352,18 +356,47 @@ size_t s2_attn_decode_workspace_bytes(int32_t nseq, int32_t heads, int32_t head_
   return ((items * (head_dim + 2) * sizeof(float) + 255) / 256) * 256;
 }
 
-int s2_attn_decode(const s2_layout_params* lp, const s2_decode_args* a, float scale, void* workspace,
-                   size_t workspace_bytes, void* stream) {
-  if (!lp || !a) return S2_ERR_NULL;
-  if (!a->q || !a->k_cache || !a->v_cache || !a->seq_lens || !a->o) return S2_ERR_NULL;
-  if (!(scale > 0.f) || !std::isfinite(scale)) return S2_ERR_BAD_PARAM;
-  if (lp->block_size != 16 && lp->block_size != 32 && lp->block_size != 64 && lp->block_size != 128) return S2_ERR_BAD_PARAM;
+namespace {
+
+bool good_block_size(int S) { return S == 16 || S == 32 || S == 64 || S == 128; }
+
+// The pattern a decode call follows: the closed form of `lp`, or, when `layout` is given, the
+// layout's own rows (then lp = &layout->p supplies S and the head count only).
+int check_pattern(const s2_layout_params* lp, const s2_layout* layout, int heads, int64_t max_len) {
+  if (!good_block_size(lp->block_size)) return S2_ERR_BAD_PARAM;
+  if (heads != lp->num_heads) return S2_ERR_SHAPE;
+  if (layout) {
+    if (max_len > (int64_t)lp->num_blocks * lp->block_size) return S2_ERR_SHAPE;
+    return layout_on_current_device(layout) ? S2_OK : S2_ERR_NO_DEVICE;
+  }
   if (lp->dense != 0 && lp->dense != 1) return S2_ERR_BAD_PARAM;
   if (!lp->dense && (lp->local_blocks < 1 || lp->stride < 0 || lp->window_blocks < 0)) return S2_ERR_BAD_PARAM;
   if (lp->head_index_base < 0) return S2_ERR_BAD_PARAM;
+  return S2_OK;
+}
+
+void set_pattern(s2::DecodeParams& p, const s2_layout_params* lp, const s2_layout* layout) {
+  p.block_size = lp->block_size;
+  p.local_blocks = lp->local_blocks;
+  p.stride = lp->stride;
+  p.window_blocks = lp->window_blocks;
+  p.dense = lp->dense;
+  p.head_index_base = lp->head_index_base;
+  if (layout) {
+    p.row_ptr = layout->d_row_ptr;
+    p.col_idx = layout->d_col_idx;
+    p.num_blocks = lp->num_blocks;
+  }
+}
+
+int decode_contiguous(const s2_layout_params* lp, const s2_layout* layout, const s2_decode_args* a, float scale,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+  if (!a->q || !a->k_cache || !a->v_cache || !a->seq_lens || !a->o) return S2_ERR_NULL;
+  if (!(scale > 0.f) || !std::isfinite(scale)) return S2_ERR_BAD_PARAM;
   if (a->nseq < 1 || a->heads < 1 || a->max_len < 1) return S2_ERR_SHAPE;
-  if (a->heads != lp->num_heads) return S2_ERR_SHAPE;
   if (a->head_dim != 64 && a->head_dim != 128) return S2_ERR_SHAPE;
+  int st = check_pattern(lp, layout, a->heads, a->max_len);
+  if (st != S2_OK) return st;
   if (a->num_splits < 0 || a->num_splits > 64) return S2_ERR_BAD_PARAM;
   const int64_t strides[3] = {a->kv_stride_seq, a->kv_stride_head, a->kv_stride_tok};
   for (int64_t s : strides)
@@ -398,28 +431,21 @@ int s2_attn_decode(const s2_layout_params* lp, const s2_decode_args* a, float sc
   p.kv_st = a->kv_stride_tok;
   p.scale = scale;
   p.scale_log2e = scale * 1.4426950408889634f;
-  p.block_size = lp->block_size;
-  p.local_blocks = lp->local_blocks;
-  p.stride = lp->stride;
-  p.window_blocks = lp->window_blocks;
-  p.dense = lp->dense;
-  p.head_index_base = lp->head_index_base;
+  set_pattern(p, lp, layout);
   return hip_ok(s2::launch_decode(p, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
 }
 
-int s2_attn_decode_paged(const s2_layout_params* lp, const s2_paged_decode_args* a, float scale,
-                         void* workspace, size_t workspace_bytes, void* stream) {
-  if (!lp || !a) return S2_ERR_NULL;
+int decode_paged(const s2_layout_params* lp, const s2_layout* layout, const s2_paged_decode_args* a, float scale,
+                 void* workspace, size_t workspace_bytes, void* stream) {
   if (!a->q || !a->k_pages || !a->v_pages || !a->block_table || !a->seq_lens || !a->o) return S2_ERR_NULL;
   if (!(scale > 0.f) || !std::isfinite(scale)) return S2_ERR_BAD_PARAM;
-  if (lp->block_size != 16 && lp->block_size != 32 && lp->block_size != 64 && lp->block_size != 128) return S2_ERR_BAD_PARAM;
-  if (lp->dense != 0 && lp->dense != 1) return S2_ERR_BAD_PARAM;
-  if (!lp->dense && (lp->local_blocks < 1 || lp->stride < 0 || lp->window_blocks < 0)) return S2_ERR_BAD_PARAM;
-  if (lp->head_index_base < 0) return S2_ERR_BAD_PARAM;
+  if (!good_block_size(lp->block_size)) return S2_ERR_BAD_PARAM;
   if (a->nseq < 1 || a->heads < 1 || a->max_blocks < 1 || a->num_pages < 1) return S2_ERR_SHAPE;
   if ((int64_t)a->max_blocks * lp->block_size > std::numeric_limits<int32_t>::max()) return S2_ERR_SHAPE;
-  if (a->heads != lp->num_heads) return S2_ERR_SHAPE;
   if (a->head_dim != 64 && a->head_dim != 128) return S2_ERR_SHAPE;
+  const int max_len = a->max_blocks * lp->block_size;
+  int st = check_pattern(lp, layout, a->heads, max_len);
+  if (st != S2_OK) return st;
   if (a->num_splits < 0 || a->num_splits > 64) return S2_ERR_BAD_PARAM;
   if (a->page_stride < 0 || (a->page_stride & 7) != 0 || a->tok_stride < 0 || (a->tok_stride & 7) != 0)
     return S2_ERR_ALIGN;
@@ -429,7 +455,6 @@ int s2_attn_decode_paged(const s2_layout_params* lp, const s2_paged_decode_args*
       (reinterpret_cast<uintptr_t>(a->block_table) & 3u) != 0 ||
       (reinterpret_cast<uintptr_t>(a->missing) & 3u) != 0)
     return S2_ERR_ALIGN;
-  const int max_len = a->max_blocks * lp->block_size;
   const int splits = a->num_splits > 0 ? a->num_splits
                                        : s2_attn_decode_default_splits(a->nseq, a->heads, max_len);
   const size_t need = s2_attn_decode_workspace_bytes(a->nseq, a->heads, a->head_dim, max_len, splits);
@@ -456,12 +481,7 @@ int s2_attn_decode_paged(const s2_layout_params* lp, const s2_paged_decode_args*
   p.kv_st = a->tok_stride;
   p.scale = scale;
   p.scale_log2e = scale * 1.4426950408889634f;
-  p.block_size = lp->block_size;
-  p.local_blocks = lp->local_blocks;
-  p.stride = lp->stride;
-  p.window_blocks = lp->window_blocks;
-  p.dense = lp->dense;
-  p.head_index_base = lp->head_index_base;
+  set_pattern(p, lp, layout);
   p.block_table = a->block_table;
   p.missing = a->missing;
   p.max_blocks = a->max_blocks;
@@ -469,11 +489,59 @@ int s2_attn_decode_paged(const s2_layout_params* lp, const s2_paged_decode_args*
   return hip_ok(s2::launch_decode(p, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
 }
 
+}  // namespace
+
+int s2_attn_decode(const s2_layout_params* lp, const s2_decode_args* a, float scale, void* workspace,
+                   size_t workspace_bytes, void* stream) {
+  if (!lp || !a) return S2_ERR_NULL;
+  return decode_contiguous(lp, nullptr, a, scale, workspace, workspace_bytes, stream);
+}
+
+int s2_attn_decode_paged(const s2_layout_params* lp, const s2_paged_decode_args* a, float scale,
+                         void* workspace, size_t workspace_bytes, void* stream) {
+  if (!lp || !a) return S2_ERR_NULL;
+  return decode_paged(lp, nullptr, a, scale, workspace, workspace_bytes, stream);
+}
+
+int s2_attn_decode_layout(const s2_layout* layout, const s2_decode_args* a, float scale, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  if (!layout || !a) return S2_ERR_NULL;
+  return decode_contiguous(&layout->p, layout, a, scale, workspace, workspace_bytes, stream);
+}
+
+int s2_attn_decode_paged_layout(const s2_layout* layout, const s2_paged_decode_args* a, float scale,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+  if (!layout || !a) return S2_ERR_NULL;
+  return decode_paged(&layout->p, layout, a, scale, workspace, workspace_bytes, stream);
+}
+
+int s2_layout_resident_blocks(const s2_layout* L, int32_t head, int32_t length, int32_t* blocks,
+                              int32_t capacity, int32_t* count) {
+  if (!L || !count) return S2_ERR_NULL;
+  if (capacity < 0 || (capacity > 0 && !blocks)) return S2_ERR_NULL;
+  const int B = L->p.num_blocks, S = L->p.block_size;
+  if (head < 0 || head >= L->p.num_heads || length < 1 || (int64_t)length > (int64_t)B * S)
+    return S2_ERR_BAD_PARAM;
+  // A block among 0..i (i = row of the newest token) stays while row i or any later row keeps it:
+  // walk each such column's list of attending rows (ascending) and look at its last entry.
+  const int i = (length - 1) / S;
+  int64_t n = 0;
+  for (int j = 0; j <= i; ++j) {
+    const int32_t lo = L->col_ptr[(size_t)head * B + j], hi = L->col_ptr[(size_t)head * B + j + 1];
+    if (hi > lo && L->row_idx[hi - 1] >= i) {
+      if (n < capacity) blocks[n] = j;
+      ++n;
+    }
+  }
+  *count = (int32_t)n;
+  return n > capacity ? S2_ERR_OVERFLOW : S2_OK;
+}
+
 int s2_kv_resident_blocks(const s2_layout_params* lp, int32_t head, int32_t length, int32_t* blocks,
                           int32_t capacity, int32_t* count) {
   if (!lp || !count) return S2_ERR_NULL;
   if (capacity < 0 || (capacity > 0 && !blocks)) return S2_ERR_NULL;
-  if (lp->block_size != 16 && lp->block_size != 32 && lp->block_size != 64 && lp->block_size != 128) return S2_ERR_BAD_PARAM;
+  if (!good_block_size(lp->block_size)) return S2_ERR_BAD_PARAM;
   if (lp->dense != 0 && lp->dense != 1) return S2_ERR_BAD_PARAM;
   if (!lp->dense && (lp->local_blocks < 1 || lp->stride < 0 || lp->window_blocks < 0)) return S2_ERR_BAD_PARAM;
   if (lp->head_index_base < 0 || lp->num_heads < 1) return S2_ERR_BAD_PARAM;

@@ -5,6 +5,8 @@
 // issues 16-byte loads, a row of K or V is covered by D/8 adjacent lanes, and both the K and V
 // loads of a 64-token unit are in flight before the first score is needed.
 //
+// A caller-supplied pattern replaces the closed form by row (L-1) div S of the layout's lists.
+//
 // Paged cache (PAGED = true): a kept block's rows are found through the block table instead of
 // by offset into a contiguous cache; nothing else changes, since a page is one contiguous block.
 //
@@ -23,10 +25,12 @@ namespace {
 
 constexpr float kNegInf = -__builtin_inff();
 
-// Kept blocks of block row i, in ascending order, as (stripe run, local run).
+// Kept blocks of block row i, in ascending order, as (stripe run, local run), or as a list.
 struct RowBlocks {
   int first_stripe, n_stripe, stride, local_lo, count;
+  const int32_t* cols;  // caller-supplied pattern: the row's list; nullptr = closed form
   __device__ int block(int n) const {
+    if (cols) return cols[n];
     return n < n_stripe ? first_stripe + n * stride : local_lo + (n - n_stripe);
   }
 };
@@ -36,6 +40,14 @@ __device__ inline RowBlocks row_blocks(const DecodeParams& p, int head, int i) {
   r.stride = p.stride;
   r.first_stripe = 0;
   r.n_stripe = 0;
+  r.cols = nullptr;
+  r.local_lo = 0;
+  if (p.row_ptr) {
+    const int32_t lo = p.row_ptr[(int64_t)head * p.num_blocks + i];
+    r.cols = p.col_idx + lo;
+    r.count = p.row_ptr[(int64_t)head * p.num_blocks + i + 1] - lo;
+    return r;
+  }
   if (p.dense) {
     r.local_lo = 0;
     r.count = i + 1;

@@ -59,6 +59,11 @@ struct DecodeParams {
   const int32_t* block_table;  // [nseq, heads, max_blocks], nullptr = contiguous cache
   int32_t* missing;            // optional counter of kept blocks that are not resident
   int max_blocks, num_pages;
+  // caller-supplied pattern: the kept blocks of row i of head h are
+  // col_idx[row_ptr[h*num_blocks + i] .. row_ptr[h*num_blocks + i + 1]); nullptr = closed form
+  const int32_t* row_ptr;
+  const int32_t* col_idx;
+  int num_blocks;
 };
 
 // Each returns the hipError_t of the launch (hipGetLastError after the launch).

@@ -44,6 +44,8 @@ struct s2_layout {
   int covers_all = 0;
   bool on_device = false;
   int device = -1;
+  int32_t* d_row_ptr = nullptr;  // device copies of the compressed rows (decode reads one row of them)
+  int32_t* d_col_idx = nullptr;
   s2::TileList fwd_tiles; // row groups  -> kept KV blocks   (forward)
   s2::TileList q_tiles;   // row groups  -> kept KV blocks   (dQ pass)
   s2::TileList kv_tiles;  // column groups -> attending Q blocks (dK/dV pass)

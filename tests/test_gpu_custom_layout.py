@@ -1,4 +1,4 @@
-"""GPU parity of forward and backward under caller-supplied per-head patterns (s2_layout_from_csr):
+"""GPU parity of forward, backward and decode under caller-supplied per-head patterns (s2_layout_from_csr):
 attention sink, the same shards for all heads, per-context-range and random patterns (sections 3
 and 5.1) against the fp64 oracle evaluated on the same block mask."""
 
@@ -95,6 +95,92 @@ def test_custom_layout_equal_to_the_rule_gives_identical_bits():
         o = torch.empty_like(q)
         lse = torch.empty((1, H, N), dtype=torch.float32, device="cuda")
         B.s2_attn_fwd(lay, q, k, v, o, lse, w.scale)
+        torch.cuda.synchronize()
+        outs.append((o.clone(), lse.clone()))
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+
+
+DECODE_CASES = {
+    # name: (workload, heads, block size, layout blocks, mask builder)
+    "sink_S64": ("7b_decode", 4, 64, 20, lambda H, Bk: orc.with_sink(orc.block_mask(H, Bk, 3, 5), 2)),
+    "random_S64": ("7b_decode", 3, 64, 18, lambda H, Bk: _random_mask(11, H, Bk, 0.4)),
+    "per_range_S128": ("7b_decode", 4, 128, 12, _per_range_mask),
+    "random_S16": ("7b_decode", 3, 16, 64, lambda H, Bk: _random_mask(12, H, Bk, 0.15)),
+    "random_S32_D64": ("tiny", 2, 32, 30, lambda H, Bk: _random_mask(13, H, Bk, 0.5)),
+}
+
+
+@pytest.mark.parametrize("paged", [False, True])
+@pytest.mark.parametrize("case", sorted(DECODE_CASES))
+def test_custom_layout_decode(case, paged):
+    wname, H, S, Bk, build = DECODE_CASES[case]
+    w = synth.WORKLOADS[wname]
+    M = build(H, Bk)
+    max_len = Bk * S
+    lens = np.array([1, S - 1, S, S + 1, max_len // 2 + 3, max_len - 1, max_len], dtype=np.int32)
+    nseq = len(lens)
+    print("custom decode case", case, "paged", paged, "H", H, "S", S, "B", Bk, flush=True)
+    qb, kcb, vcb, lens = synth.decode_inputs_small(w, nseq, H, max_len, lengths=lens)
+    row_ptr, col_idx, _, _ = orc.compressed_layout(M)
+    lay = B.s2_layout_from_csr(H, Bk, S, row_ptr, col_idx)
+    q = G.to_dev(qb)
+    sl = torch.from_numpy(lens).cuda()
+    o = torch.empty_like(q)
+    lse = torch.empty((nseq, H), dtype=torch.float32, device="cuda")
+    ws = torch.empty(B.s2_attn_decode_workspace_bytes(nseq, H, w.head_dim, max_len, 3), dtype=torch.uint8,
+                     device="cuda")
+    f = G.bits_f64
+    if paged:
+        # hold exactly what the layout says must stay: blocks kept by later rows only are resident
+        # too, blocks nobody will read again are gone
+        resident = [[B.s2_layout_resident_blocks(lay, h, int(L)) for h in range(H)] for L in lens]
+        for b, L in enumerate(lens):
+            for h in range(H):
+                assert resident[b][h] == orc.resident_blocks_mask(M[h], int(L), S)
+        table, num_pages = synth.page_table(resident, Bk, index=w.index)
+        kpool = synth.pages_from_cache(kcb, table, num_pages, S)
+        vpool = synth.pages_from_cache(vcb, table, num_pages, S)
+        missing = torch.zeros(1, dtype=torch.int32, device="cuda")
+        B.s2_attn_decode_paged_layout(lay, q, G.to_dev(kpool), G.to_dev(vpool), torch.from_numpy(table).cuda(), sl,
+                                      o, lse, w.scale, ws, missing=missing, num_splits=3)
+        torch.cuda.synchronize()
+        assert int(missing.item()) == 0
+    else:
+        B.s2_attn_decode_layout(lay, q, G.to_dev(kcb), G.to_dev(vcb), sl, o, lse, w.scale, ws, max_len, num_splits=3)
+        torch.cuda.synchronize()
+    for b in range(nseq):
+        for h in range(H):
+            if paged:
+                ref, ref_lse = orc.paged_decode_row_mask(f(qb)[b, h], f(kpool), f(vpool), table[b, h], int(lens[b]),
+                                                         M[h], S, w.scale)
+            else:
+                ref, ref_lse = orc.decode_row_mask(f(qb)[b, h], f(kcb)[b, h], f(vcb)[b, h], int(lens[b]), M[h], S,
+                                                   w.scale)
+            assert G.o_excess(G.to_f64(o[b, h]), ref) <= 0, (b, h)
+            assert abs(float(lse[b, h]) - ref_lse) <= LSE_TOL, (b, h)
+
+
+def test_layout_decode_of_the_rule_gives_the_closed_form_bits():
+    # a layout built from section 4.2's rule must decode exactly like the closed-form entry point
+    w = synth.WORKLOADS["7b_decode"]
+    H, S, Bk = 5, 64, 24
+    max_len = Bk * S
+    lens = np.array([1, 64, 65, 1000, max_len], dtype=np.int32)
+    qb, kcb, vcb, lens = synth.decode_inputs_small(w, len(lens), H, max_len, lengths=lens)
+    params = B.layout_params(H, Bk, S, 3, 6)
+    lay = B.s2_layout_build(params)
+    q, kc, vc = G.to_dev(qb), G.to_dev(kcb), G.to_dev(vcb)
+    sl = torch.from_numpy(lens).cuda()
+    ws = torch.empty(B.s2_attn_decode_workspace_bytes(len(lens), H, w.head_dim, max_len, 4), dtype=torch.uint8,
+                     device="cuda")
+    outs = []
+    for use_layout in (False, True):
+        o = torch.empty_like(q)
+        lse = torch.empty((len(lens), H), dtype=torch.float32, device="cuda")
+        if use_layout:
+            B.s2_attn_decode_layout(lay, q, kc, vc, sl, o, lse, w.scale, ws, max_len, num_splits=4)
+        else:
+            B.s2_attn_decode(params, q, kc, vc, sl, o, lse, w.scale, ws, max_len, num_splits=4)
         torch.cuda.synchronize()
         outs.append((o.clone(), lse.clone()))
     assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])

@@ -294,3 +294,48 @@ def test_layout_from_csr_rejects_bad_rows():
     assert call(1, 3, 64, [0, 1, 3, 5], [0, 0, 2, 0, 2]) == -2      # above the diagonal
     assert call(1, 3, 64, [0, 1, 3, 4], [0, 0, 1, 1]) == -2         # diagonal missing in row 2
     assert call(1, 3, 64, [0, 1, 3, 5], [0, 0, 1, -1, 2]) == -2     # negative column
+
+
+def test_layout_resident_blocks_bit_exact_against_the_oracle():
+    # the scan of the layout's later rows, for arbitrary patterns and for the section 4.2 rule
+    rng = np.random.default_rng(33)
+    masks = [_random_causal_mask(rng, 3, int(Bk), float(d)) for Bk, d in ((1, 0.5), (7, 0.3), (20, 0.1), (16, 0.9))]
+    masks.append(orc.with_sink(orc.block_mask(4, 24, 3, 4), 2))
+    for M in masks:
+        H, Bk, _ = M.shape
+        row_ptr, col_idx, _, _ = orc.compressed_layout(M)
+        for S in (16, 64) if Bk % 2 == 0 else (64,):
+            lay = B.s2_layout_from_csr(H, Bk, S, row_ptr, col_idx)
+            for h in range(H):
+                for L in sorted(x for x in {1, S - 1, S, S + 1, (Bk * S) // 2, Bk * S - 1, Bk * S} if 1 <= x <= Bk * S):
+                    assert B.s2_layout_resident_blocks(lay, h, L) == orc.resident_blocks_mask(M[h], L, S), (h, L, S)
+    # a layout built from the rule: same answer as the closed-form helper away from the layout's end
+    p = B.layout_params(4, 64, 32, 3, 5)
+    lay = B.s2_layout_build(p)
+    for h in range(4):
+        for L in (1, 32, 33, 500, 1024):
+            assert B.s2_layout_resident_blocks(lay, h, L) == B.s2_kv_resident_blocks(p, h, L)
+
+
+def test_layout_decode_errors_without_launch():
+    lib = B.lib()
+    lay = B.s2_layout_build(B.layout_params(2, 8, 64, 2, 4))
+    n = C.c_int32(-1)
+    buf = (C.c_int32 * 2)()
+    assert lib.s2_layout_resident_blocks(None, 0, 10, buf, 2, C.byref(n)) == -1
+    assert lib.s2_layout_resident_blocks(lay.handle, 0, 10, buf, 2, None) == -1
+    assert lib.s2_layout_resident_blocks(lay.handle, 0, 10, None, 2, C.byref(n)) == -1
+    assert lib.s2_layout_resident_blocks(lay.handle, 2, 10, buf, 2, C.byref(n)) == -2
+    assert lib.s2_layout_resident_blocks(lay.handle, 0, 0, buf, 2, C.byref(n)) == -2
+    assert lib.s2_layout_resident_blocks(lay.handle, 0, 8 * 64 + 1, buf, 2, C.byref(n)) == -2   # beyond the layout
+    assert lib.s2_layout_resident_blocks(lay.handle, 0, 8 * 64, buf, 1, C.byref(n)) == -8 and n.value >= 2
+    a = B.DecodeArgs(4096, 4096, 4096, 4096, 4096, None, 1, 2, 128, 8 * 64 + 1, 1, 1024, 512, 128)
+    assert lib.s2_attn_decode_layout(None, C.byref(a), 1.0, None, 0, None) == -1
+    assert lib.s2_attn_decode_layout(lay.handle, None, 1.0, None, 0, None) == -1
+    assert lib.s2_attn_decode_layout(lay.handle, C.byref(a), 1.0, None, 0, None) == -3         # cache longer than layout
+    a.heads = 3
+    a.max_len = 64
+    assert lib.s2_attn_decode_layout(lay.handle, C.byref(a), 1.0, None, 0, None) == -3         # head count
+    pa = B.PagedDecodeArgs(4096, 4096, 4096, 4096, 4096, 4096, None, None, 1, 2, 128, 9, 4, 1, 64 * 128, 128)
+    assert lib.s2_attn_decode_paged_layout(None, C.byref(pa), 1.0, None, 0, None) == -1
+    assert lib.s2_attn_decode_paged_layout(lay.handle, C.byref(pa), 1.0, None, 0, None) == -3   # 9 blocks > 8
