@@ -24,6 +24,8 @@ What each function follows:
   plus causality inside the diagonal block.
 * ``attention_forward`` / ``attention_backward`` - softmax attention over the
   kept keys only (section 3.2) and its analytic gradient.
+* ``attention_forward_varlen`` - the forward on a packed batch of sequences of
+  different lengths, each an independent problem (serving prefill, section 5.3).
 * ``decode_row`` - one decoding step against a cache (section 4.1): the last
   row of the same masked attention.
 * ``resident_blocks`` / ``paged_decode_row`` - section 4.1's KV-efficient
@@ -296,6 +298,29 @@ def attention_backward(q, k, v, dO, M, block_size, scale):
             dQ[b, h], dK[b, h], dV[b, h], O[b, h], LSE[b, h] = attention_backward_head(
                 q[b, h], k[b, h], v[b, h], dO[b, h], M[h], block_size, scale)
     return dQ, dK, dV, O, LSE
+
+
+def attention_forward_varlen(q, k, v, cu_seqlens, M, block_size, scale):
+    """Packed batch of sequences of different lengths (serving prefill, section 5.3).
+
+    q,k,v [H,total,D]; sequence s owns rows cu_seqlens[s] .. cu_seqlens[s+1]-1 and
+    is an attention problem of its own: its first token is position 0 of the mask,
+    its last block may be partial, and it sees no other sequence.  M [H,B,B] needs
+    B >= ceil(longest length / S).  Returns O [H,total,D], LSE [H,total]; rows that
+    belong to no sequence (after cu_seqlens[-1]) come back as NaN.
+    """
+    q, k, v = np.asarray(q), np.asarray(k), np.asarray(v)
+    H, total, _ = q.shape
+    cu = [int(x) for x in cu_seqlens]
+    O = np.full(v.shape, np.nan, dtype=np.float64)
+    LSE = np.full((H, total), np.nan, dtype=np.float64)
+    for lo, hi in zip(cu[:-1], cu[1:]):
+        if hi == lo:
+            continue
+        for h in range(H):
+            O[h, lo:hi], LSE[h, lo:hi] = attention_forward_head(q[h, lo:hi], k[h, lo:hi], v[h, lo:hi], M[h],
+                                                                block_size, scale)
+    return O, LSE
 
 
 def forward_rows(q_rows, row_index, k, v, Mh, block_size, scale):
