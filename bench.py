@@ -302,6 +302,50 @@ def bench_decode_paged(w, steps, warmup):
                 algorithmic_gb=(kv_bytes + other) / 1e9, hbm_gbs=gbs, frac_hbm_peak=gbs / PEAK_HBM_GBS)
 
 
+def bench_prefill_varlen(w, steps, warmup, nseq=12, min_len=1024):
+    """A serving prefill batch: `nseq` prompts of different lengths packed into one tensor, one
+    launch of the variable-length forward; beside it the same prompts padded to the longest."""
+    import torch
+    from paper_2407_17678_amd import binding as B
+    from paper_2407_17678_amd import synth
+    H, D, S = w.heads, w.head_dim, w.block_size
+    lens = synth.prefill_lengths(w, nseq, min_len)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    total = int(cu[-1])
+    lay = B.s2_layout_build(B.layout_params(H, w.num_blocks, S, w.local_blocks, w.stride, 0, w.window_blocks, 0))
+    view = B.s2_layout_get(lay)
+    # unmasked pairs: per block row, (kept blocks - 1) full blocks of S keys plus the causal diagonal
+    row_blocks = np.diff(view["row_ptr"]).reshape(H, w.num_blocks).astype(np.int64)
+    pairs = 0
+    for L in lens.tolist():
+        full, rem = divmod(L, S)
+        pairs += int(((row_blocks[:, :full] - 1) * S * S + S * (S + 1) // 2).sum())
+        if rem:
+            pairs += int(((row_blocks[:, full] - 1) * S * rem + rem * (rem + 1) // 2).sum())
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.BASE_SEED + w.index)
+    q, k, v = (torch.randn((1, H, total, D), device="cuda", generator=gen).to(torch.bfloat16) for _ in range(3))
+    o = torch.empty_like(q)
+    lse = torch.empty((H, total), dtype=torch.float32, device="cuda")
+    cud = torch.from_numpy(cu).cuda()
+    run = lambda: B.s2_attn_fwd_varlen(lay, q, k, v, o, lse, cud, w.seqlen, w.scale)
+    prewarm(run)
+    ms = time_events(run, steps, warmup)
+    # what a caller without the packed entry point does: every prompt padded to the longest one
+    pad_len = -(-int(lens.max()) // 128) * 128
+    lay_p = B.s2_layout_build(B.layout_params(H, pad_len // S, S, w.local_blocks, w.stride, 0, w.window_blocks, 0))
+    qp, kp, vp = (torch.randn((nseq, H, pad_len, D), device="cuda", generator=gen).to(torch.bfloat16) for _ in range(3))
+    op = torch.empty_like(qp)
+    lsep = torch.empty((nseq, H, pad_len), dtype=torch.float32, device="cuda")
+    run_p = lambda: B.s2_attn_fwd(lay_p, qp, kp, vp, op, lsep, w.scale)
+    ms_pad = time_events(run_p, max(3, steps // 2), 2)
+    tf = 4.0 * D * pairs / (ms * 1e-3) / 1e12
+    return dict(workload=w.name + "_prefill_varlen", nseq=nseq, heads=H, head_dim=D, block_size=S,
+                lengths=lens.tolist(), total_tokens=total, ms=ms, unmasked_pairs=pairs, tflops=tf,
+                pct_mfma_peak=100.0 * tf / PEAK_BF16_TFLOPS, ms_padded_to_longest=ms_pad,
+                speedup_vs_padded=ms_pad / ms)
+
+
 def bench_decode(w, steps, warmup):
     import torch
     from paper_2407_17678_amd import binding as B
@@ -350,7 +394,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="7b_32k", choices=["tiny", "1p3b_8k", "7b_32k", "7b_128k", "7b_decode", "7b_decode_paged"])
+    ap.add_argument("--workload", default="7b_32k", choices=["tiny", "1p3b_8k", "7b_32k", "7b_128k", "7b_decode", "7b_decode_paged",
+                             "7b_prefill_varlen"])
     ap.add_argument("--cpu-sample-tokens", type=int, default=32768)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
@@ -375,7 +420,8 @@ def main():
     B.lib()
     torch.cuda.set_device(0)
     paged = args.workload == "7b_decode_paged"
-    w = synth.WORKLOADS["7b_decode" if paged else args.workload]
+    varlen = args.workload == "7b_prefill_varlen"
+    w = synth.WORKLOADS["7b_decode" if paged else "7b_32k" if varlen else args.workload]
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 255)
         dst = torch.empty_like(src)
@@ -383,6 +429,19 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    if varlen:
+        d = bench_prefill_varlen(w, args.steps, args.warmup)
+        out = {"metric": "effective sparse-attn TFLOP/s, forward on a packed variable-length prefill batch",
+               "value": d["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+               "ms_per_step": d["ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+               "dtype": "bf16", "data": "synthetic", "config": d,
+               "roofline": {"kernel": "fwd_kernel (variable-length)", "bound": "mfma", "achieved": d["tflops"],
+                            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": d["tflops"] / PEAK_BF16_TFLOPS,
+                            "traffic": measured_traffic(d["workload"], "fwd_kernel")},
+               "cpu_baseline": None}
+        print(json.dumps(out))
+        return
 
     if w.kind == "decode":
         d = bench_decode_paged(w, args.steps, args.warmup) if paged else bench_decode(w, args.steps, args.warmup)
@@ -425,6 +484,7 @@ def main():
             torch.cuda.empty_cache()
         extra["7b_decode"] = bench_decode(synth.WORKLOADS["7b_decode"], 20, 3)
         extra["7b_decode_paged"] = bench_decode_paged(synth.WORKLOADS["7b_decode"], 20, 3)
+        extra["7b_prefill_varlen"] = bench_prefill_varlen(synth.WORKLOADS["7b_32k"], 10, 2)
 
     out = {
         "metric": "effective sparse-attn TFLOP/s fwd+bwd (% MFMA peak) + speedup vs dense causal"

@@ -176,6 +176,20 @@ int s2_attn_fwd(const s2_layout* layout, const s2_tensors* t, float scale, void*
 int s2_attn_fwd_rows(const s2_layout* layout, const s2_tensors* t, int32_t q_row_start,
                      int32_t q_rows, float scale, void* stream);
 
+/* The forward for a packed batch of sequences of different lengths (serving prefill batches,
+ * section 5.3): t->batch must be 1 and t->seqlen is the number of rows in q, k, v, o; lse is
+ * [heads, t->seqlen].  cu_seqlens is DEVICE int32 [num_seqs + 1], ascending from 0: sequence s
+ * owns rows cu_seqlens[s] .. cu_seqlens[s+1]-1 and is attended on its own, its first token at
+ * position 0 of the mask; any length >= 0 (no multiple of the block size is asked for).  No
+ * length may exceed max_seqlen, and max_seqlen <= B*S of the layout.  The array is read by the
+ * kernel only: a length above max_seqlen is cut there, rows outside the tensors are never
+ * touched, and rows that belong to no sequence are left as they were.  Each row comes out as
+ * s2_attn_fwd gives it for the same sequence alone.  Errors: NULL, SHAPE (batch != 1, head
+ * count, num_seqs < 1, max_seqlen < 1 or beyond the layout), ALIGN, BAD_PARAM (scale),
+ * NO_DEVICE, HIP. */
+int s2_attn_fwd_varlen(const s2_layout* layout, const s2_tensors* t, const int32_t* cu_seqlens,
+                       int32_t num_seqs, int32_t max_seqlen, float scale, void* stream);
+
 /* ---- backward (gradient of the above) ---------------------------------------------------- */
 
 /* Given q,k,v,o,lse,d_o writes dq,dk,dv (bf16; fp32 accumulation).  workspace is DEVICE memory

@@ -278,6 +278,31 @@ int s2_attn_fwd_rows(const s2_layout* layout, const s2_tensors* t, int32_t q_row
   return hip_ok(s2::launch_fwd(p, false, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
 }
 
+int s2_attn_fwd_varlen(const s2_layout* layout, const s2_tensors* t, const int32_t* cu_seqlens,
+                       int32_t num_seqs, int32_t max_seqlen, float scale, void* stream) {
+  if (!layout || !cu_seqlens) return S2_ERR_NULL;
+  int st = check_tensors(t, false, scale);
+  if (st != S2_OK) return st;
+  if (t->batch != 1 || t->heads != layout->p.num_heads) return S2_ERR_SHAPE;
+  if (num_seqs < 1 || max_seqlen < 1) return S2_ERR_SHAPE;
+  if ((int64_t)max_seqlen > (int64_t)layout->p.num_blocks * layout->p.block_size) return S2_ERR_SHAPE;
+  if ((int64_t)num_seqs * t->heads > std::numeric_limits<int32_t>::max() / 2) return S2_ERR_SHAPE;
+  if ((reinterpret_cast<uintptr_t>(cu_seqlens) & 3u) != 0) return S2_ERR_ALIGN;
+  if (!layout_on_current_device(layout)) return S2_ERR_NO_DEVICE;
+  s2::AttnParams p = make_params(t, scale);
+  p.batch = num_seqs;
+  p.q_rows = max_seqlen;
+  p.cu_seqlens = cu_seqlens;
+  p.block_size = layout->p.block_size;
+  p.fwd_tiles = dev_tiles(layout->fwd_tiles);
+  p.q_tiles = dev_tiles(layout->q_tiles);
+  p.kv_tiles = dev_tiles(layout->kv_tiles);
+  // one grid slot per (sequence, head, 128-row tile of the longest length allowed)
+  const int64_t slots = 8 * (((int64_t)num_seqs * t->heads + 7) / 8) * ((max_seqlen + s2::kFwdBM - 1) / s2::kFwdBM);
+  if (slots > std::numeric_limits<int32_t>::max()) return S2_ERR_SHAPE;
+  return hip_ok(s2::launch_fwd(p, false, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
+}
+
 int s2_attn_bwd_stages(const s2_layout* layout, const s2_tensors* t, float scale, void* workspace,
                        size_t workspace_bytes, int stages, void* stream) {
   if (!layout) return S2_ERR_NULL;

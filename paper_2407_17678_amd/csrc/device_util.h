@@ -144,6 +144,24 @@ struct DmaTile {
     return pl;
   }
 
+  // The same for a chunk of which only the first `rows_valid` rows exist (the ragged end of a
+  // sequence): loads of later rows fetch the last existing row instead; nothing may use them.
+  __device__ static __forceinline__ Plan plan_rows(int64_t row_stride, int wave, int lane, int rows_valid) {
+    Plan pl;
+    const int last = max(rows_valid, 1) - 1;
+#pragma unroll
+    for (int n = 0; n < kPerWave; ++n) {
+      const int instr = min(4 * n + wave, kInstr - 1);
+      const int pos = instr * 1024 + lane * 16;
+      int row = pos / (kStride * 2);
+      int piece = (pos - row * kStride * 2) / 16;
+      if (piece >= D / 8) piece -= D / 8;
+      row = min(min(row, ROWS - 1), last);
+      pl.goff[n] = (uint32_t)(row * row_stride * 2) + 16 * piece;
+    }
+    return pl;
+  }
+
   // One of the kPerWave loads of a chunk, so that a kernel can spread them between MFMAs.
   // Complete after s_waitcnt vmcnt(0).
   __device__ static __forceinline__ void issue_one(const Plan& pl, int n, const uint16_t* gbase,

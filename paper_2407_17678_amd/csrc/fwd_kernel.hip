@@ -28,7 +28,12 @@ constexpr float kNegInf = -__builtin_inff();
 // CH = keys per step (one LDS stage), 64 or 32.  With 32 a workgroup needs half the LDS and fewer
 // registers, so three workgroups fit a CU instead of two; measured, that is no faster (twice the
 // barriers for the same work), so 64 is what is instantiated.
-template <int D, bool DENSE, int CH>
+//
+// VARLEN: a packed batch of sequences of different lengths.  A workgroup finds its sequence's rows
+// in cu_seqlens and treats them as a sequence of its own; the ragged end costs a clamped load plan
+// for the chunks that reach past the last token (their keys are after every query, so the causal
+// mask already drops them) and a per-lane guard on the stores.
+template <int D, bool DENSE, int CH, bool VARLEN = false>
 __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const AttnParams p) {
   typedef DmaTile<D, CH> Tile;
   __shared__ __attribute__((aligned(16))) uint16_t sk[2][Tile::kElems];
@@ -47,8 +52,19 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
   if (!map_workgroup(blockIdx.x, p.batch * p.heads, T_run, bh, rank)) return;
   const int b = bh / p.heads, h = bh - b * p.heads;
   // longest tiles first: by the layout's order for a whole sequence, else simply last row first
-  const bool whole = p.q_row0 == 0 && T_run == T;
-  const int tile = (DENSE || !whole) ? p.q_row0 / BM + (T_run - 1 - rank) : p.fwd_tiles.order[h * T + rank];
+  const bool whole = !VARLEN && p.q_row0 == 0 && T_run == T;
+  int tile = (DENSE || !whole) ? p.q_row0 / BM + (T_run - 1 - rank) : p.fwd_tiles.order[h * T + rank];
+  // rows of the tensors before my sequence, and its length (q, o, lse rows and keys alike)
+  int row_base = 0, N = p.seqlen, n_q = p.q_rows;
+  if (VARLEN) {
+    const int lo = p.cu_seqlens[b], hi = p.cu_seqlens[b + 1];
+    row_base = min(max(lo, 0), p.seqlen);  // whatever the array holds, stay inside the tensors
+    N = min(min(max(hi - lo, 0), p.q_rows), p.seqlen - row_base);
+    n_q = N;
+    const int T_seq = (N + BM - 1) / BM;
+    if (rank >= T_seq) return;
+    tile = T_seq - 1 - rank;
+  }
   const int S = DENSE ? kChunk : p.block_size;
   // 16-token blocks: a list entry is a unit of two blocks (32 keys, one step) and my 32 query rows
   // are two mask rows, so which keys a lane may see is a 2 x 2 pattern of bits per wavefront
@@ -57,22 +73,24 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
   const int cpb = Sg / CH;  // steps per entry: a power of two, so / and % below are a shift and a mask
   const int cpb_sh = __builtin_ctz(cpb), cpb_m = cpb - 1;
 
-  const int N = p.seqlen;
   const int qw0 = tile * BM + wave * MW;  // first query row of this wavefront (sequence position)
   const int ql0 = qw0 - p.q_row0;         // the same as a row of q / o / lse
-  const bool wave_active = ql0 < p.q_rows;
+  const bool wave_active = ql0 < n_q;
   const int my_member = (qw0 / Sg) - tile * (BM / Sg);  // which mask row of the tile I am in
 
-  const uint16_t* qb = p.q + b * p.q_sb + h * p.q_sh;
-  const uint16_t* kb = p.k + b * p.kv_sb + h * p.kv_sh;
-  const uint16_t* vb = p.v + b * p.kv_sb + h * p.kv_sh;
+  const int64_t q_off = (VARLEN ? row_base * p.q_st : b * p.q_sb) + h * p.q_sh;
+  const int64_t kv_off = (VARLEN ? row_base * p.kv_st : b * p.kv_sb) + h * p.kv_sh;
+  const uint16_t* qb = p.q + q_off;
+  const uint16_t* kb = p.k + kv_off;
+  const uint16_t* vb = p.v + kv_off;
 
   // Q^T fragments stay in registers for the whole tile.
   bf16x8 qf[D / 16];
 #pragma unroll
   for (int kk = 0; kk < D / 16; ++kk) {
-    if (wave_active)
-      qf[kk] = *reinterpret_cast<const bf16x8*>(qb + (int64_t)(ql0 + l32) * p.q_st + 16 * kk + 8 * half);
+    if (wave_active)  // a lane past the ragged end reads the last row; its result is never stored
+      qf[kk] = *reinterpret_cast<const bf16x8*>(qb + (int64_t)(VARLEN ? min(ql0 + l32, N - 1) : ql0 + l32) * p.q_st +
+                                                16 * kk + 8 * half);
     else
       qf[kk] = bf16x8{};
   }
@@ -130,8 +148,14 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
     int kv0, pat;
     bool keep;
     chunk_of(0, kv0, keep, pat);
-    Tile::issue(plan, kb + (int64_t)kv0 * p.kv_st, sk[0], wave);
-    Tile::issue(plan, vb + (int64_t)kv0 * p.kv_st, sv[0], wave);
+    if (VARLEN && kv0 + CH > N) {
+      const typename Tile::Plan pr = Tile::plan_rows(p.kv_st, wave, lane, N - kv0);
+      Tile::issue(pr, kb + (int64_t)min(kv0, N - 1) * p.kv_st, sk[0], wave);
+      Tile::issue(pr, vb + (int64_t)min(kv0, N - 1) * p.kv_st, sv[0], wave);
+    } else {
+      Tile::issue(plan, kb + (int64_t)kv0 * p.kv_st, sk[0], wave);
+      Tile::issue(plan, vb + (int64_t)kv0 * p.kv_st, sv[0], wave);
+    }
   }
   wait_all_loads();
   __syncthreads();
@@ -152,11 +176,18 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
     const bool compute = wave_active && keep && kv0 <= qw0 + MW - 1;
     int kv1 = kv0;
     if (it + 1 < total) next_chunk_of(it, kv1);
-    const uint16_t* kg = kb + (int64_t)kv1 * p.kv_st;
-    const uint16_t* vg = vb + (int64_t)kv1 * p.kv_st;
+    // the plan of the loads issued in this step: the usual one, or clamped to the rows that exist
+    typename Tile::Plan pl = plan;
+    int kv1_row = kv1;
+    if (VARLEN && kv1 + CH > N) {
+      pl = Tile::plan_rows(p.kv_st, wave, lane, N - kv1);
+      kv1_row = min(kv1, N - 1);
+    }
+    const uint16_t* kg = kb + (int64_t)kv1_row * p.kv_st;
+    const uint16_t* vg = vb + (int64_t)kv1_row * p.kv_st;
     if (!compute) {
-      Tile::issue(plan, kg, kn, wave);
-      Tile::issue(plan, vg, vn, wave);
+      Tile::issue(pl, kg, kn, wave);
+      Tile::issue(pl, vg, vn, wave);
     }
 
     if (compute) {
@@ -175,8 +206,8 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
         for (int kt = 0; kt < KT; ++kt) {
           s[kt] = mfma32(kfr[kt][kk], qf[kk], s[kt]);
           const int n = KT * kk + kt;
-          if (n < PW) Tile::issue_one(plan, n, kg, kn, wave);
-          if (n >= PW && n < 2 * PW) Tile::issue_one(plan, n - PW, vg, vn, wave);
+          if (n < PW) Tile::issue_one(pl, n, kg, kn, wave);
+          if (n >= PW && n < 2 * PW) Tile::issue_one(pl, n - PW, vg, vn, wave);
         }
       static_assert(2 * PW <= KT * (D / 16), "every load has an MFMA to follow");
       if (CH == 32 && pat != 0xF) {  // 16-token blocks: drop the blocks my mask row does not keep
@@ -242,7 +273,8 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
   const float l_tot = sum_halves(l_run);
   const float inv = 1.0f / l_tot;
   const int qrow = ql0 + l32;
-  uint16_t* orow = p.o + b * p.q_sb + h * p.q_sh + (int64_t)qrow * p.q_st;
+  if (VARLEN && qrow >= N) return;  // past the ragged end of my sequence
+  uint16_t* orow = p.o + q_off + (int64_t)qrow * p.q_st;
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
@@ -252,12 +284,21 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
       for (int e = 0; e < 4; ++e) w[e] = (__bf16)(acc_o[dt][4 * g + e] * inv);
       *reinterpret_cast<bf16x4*>(orow + 32 * dt + 8 * g + 4 * half) = w;
     }
-  if (half == 0) p.lse[((int64_t)b * p.heads + h) * p.q_rows + qrow] = m_run * p.scale + __logf(l_tot);
+  const int64_t lse_row = VARLEN ? (int64_t)h * p.seqlen + row_base + qrow  // [heads, rows of the tensors]
+                                 : ((int64_t)b * p.heads + h) * p.q_rows + qrow;
+  if (half == 0) p.lse[lse_row] = m_run * p.scale + __logf(l_tot);
 }
 
 template <int D, bool DENSE>
 hipError_t launch_one(const AttnParams& p, hipStream_t stream) {
   const int grid = grid_for(p.batch * p.heads, (p.q_rows + kFwdBM - 1) / kFwdBM);
+  if (!DENSE && p.cu_seqlens) {  // packed variable-length batch (sparse layouts only)
+    if (p.block_size <= 32)
+      hipLaunchKernelGGL((fwd_kernel<D, false, 32, true>), dim3(grid), dim3(kThreads), 0, stream, p);
+    else
+      hipLaunchKernelGGL((fwd_kernel<D, false, kFwdChunk, true>), dim3(grid), dim3(kThreads), 0, stream, p);
+    return hipGetLastError();
+  }
   if (!DENSE && p.block_size <= 32)  // 16- and 32-token mask blocks: steps of 32 keys
     hipLaunchKernelGGL((fwd_kernel<D, false, 32>), dim3(grid), dim3(kThreads), 0, stream, p);
   else

@@ -32,6 +32,10 @@ struct AttnParams {
   // forward only: q, o, lse hold q_rows rows, local row r being sequence position q_row0 + r
   // (the whole sequence: q_row0 = 0, q_rows = seqlen)
   int q_row0, q_rows;
+  // packed variable-length batch (forward only; nullptr = every sequence has seqlen rows):
+  // sequence b owns rows cu_seqlens[b] .. cu_seqlens[b+1]-1 of q, k, v, o and lse; then batch is
+  // the number of sequences, seqlen the rows in the tensors and q_rows the longest length allowed
+  const int32_t* cu_seqlens;
   int64_t q_sb, q_sh, q_st;
   int64_t kv_sb, kv_sh, kv_st;
   float scale;        // softmax scale

@@ -97,6 +97,14 @@ def decode_lengths(w, nseq=None, seed_stream=1):
     return rng.integers(w.min_len, w.max_len + 1, size=n).astype(np.int32)
 
 
+def prefill_lengths(w, nseq, min_len, seed_stream=4):
+    """Prompt lengths of a serving prefill batch: log-uniform integers in [min_len, w.seqlen], no
+    rounding to blocks (the mix of a few long and many short prompts that batches of requests have)."""
+    rng = rng_for(w.index, seed_stream)
+    x = rng.uniform(np.log(min_len), np.log(w.seqlen), size=nseq)
+    return np.minimum(np.exp(x).astype(np.int64), w.seqlen).astype(np.int32)
+
+
 def decode_inputs_small(w, nseq, heads, max_len, lengths=None):
     """A host-side decode case: q [nseq,H,D], K/V cache [nseq,H,max_len,D] bits, lengths."""
     rng = rng_for(w.index, 2)

@@ -339,3 +339,20 @@ def test_layout_decode_errors_without_launch():
     pa = B.PagedDecodeArgs(4096, 4096, 4096, 4096, 4096, 4096, None, None, 1, 2, 128, 9, 4, 1, 64 * 128, 128)
     assert lib.s2_attn_decode_paged_layout(None, C.byref(pa), 1.0, None, 0, None) == -1
     assert lib.s2_attn_decode_paged_layout(lay.handle, C.byref(pa), 1.0, None, 0, None) == -3   # 9 blocks > 8
+
+
+def test_varlen_forward_argument_errors_without_launch():
+    lib = B.lib()
+    lay = B.s2_layout_build(B.layout_params(2, 8, 64, 2, 4))
+    t = _tensors(batch=1, heads=2, seqlen=700)
+    call = lambda t, cu=4096, n=3, mx=512: lib.s2_attn_fwd_varlen(lay.handle, C.byref(t), cu, n, mx, 1.0, None)
+    assert lib.s2_attn_fwd_varlen(None, C.byref(t), 4096, 3, 512, 1.0, None) == -1
+    assert call(t, cu=None) == -1
+    assert call(_tensors(batch=2, heads=2, seqlen=700)) == -3      # packed batches have batch 1
+    assert call(_tensors(batch=1, heads=3, seqlen=700)) == -3      # head count
+    assert call(t, n=0) == -3 and call(t, mx=0) == -3
+    assert call(t, mx=8 * 64 + 1) == -3                            # longer than the layout
+    assert call(t, cu=4098) == -4                                  # misaligned int32 pointer
+    import torch
+    if not torch.cuda.is_available():
+        assert call(t) == -7                                       # a host-only layout refuses to launch
