@@ -19,6 +19,8 @@
 // row-major tile: row fragments (k = feature) and LDS transpose reads (k = token).
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include "config.h"
 #include "device_util.h"
 #include "kernels.h"
@@ -479,18 +481,28 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
     }
 }
 
+// A kernel's dynamic LDS limit is a per-device attribute: remember, per device, that it is set.
+constexpr int kMaxDevices = 64;
+struct SmemSet {
+  std::atomic<unsigned char> done[kMaxDevices];
+};
+
 template <class K>
-hipError_t set_smem(K kernel, size_t bytes, bool& done) {
-  if (done) return hipSuccess;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-  if (e == hipSuccess) done = true;
+hipError_t set_smem(K kernel, size_t bytes, SmemSet& flags) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const bool tracked = dev >= 0 && dev < kMaxDevices;
+  if (tracked && flags.done[dev].load(std::memory_order_acquire)) return hipSuccess;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          (int)bytes);
+  if (e == hipSuccess && tracked) flags.done[dev].store(1, std::memory_order_release);
   return e;
 }
 
 template <int D, bool DENSE, int CH>
 hipError_t launch_one(const AttnParams& p, int stages, hipStream_t stream) {
-  static bool dq_set = false, dkdv_set = false;
+  static SmemSet dq_set, dkdv_set;  // zero-initialised
   hipError_t e = set_smem(&dq_kernel<D, DENSE, CH>, sizeof(DqSmem<D, CH>), dq_set);
   if (e != hipSuccess) return e;
   e = set_smem(&dkdv_kernel<D, DENSE, CH>, sizeof(DkvSmem<D, CH>), dkdv_set);

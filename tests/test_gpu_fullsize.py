@@ -175,3 +175,35 @@ def test_7b_decode_paged_full():
                                             w.stride, w.scale)
         assert G.o_excess(G.to_f64(o[b, h]), ref) <= 0, (b, h)
         assert abs(float(lse[b, h]) - ref_lse) <= 1e-3, (b, h)
+
+
+def test_7b_prefill_varlen_full():
+    # the packed prefill batch bench.py times (12 prompts, 87 418 tokens): sampled rows of every
+    # prompt, the ragged last rows among them, each computed by the oracle from that prompt's keys
+    w = synth.WORKLOADS["7b_32k"]
+    H, D, S = w.heads, w.head_dim, w.block_size
+    lens = synth.prefill_lengths(w, 12, 1024)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    total = int(cu[-1])
+    print("full-size case 7b_prefill_varlen", lens.tolist(), flush=True)
+    qb, kb, vb, _ = synth.train_inputs(w, heads=H, batch=1, seqlen=total)
+    lay = B.s2_layout_build(B.layout_params(H, w.num_blocks, S, w.local_blocks, w.stride))
+    q, k, v = G.to_dev(qb), G.to_dev(kb), G.to_dev(vb)
+    o = torch.empty_like(q)
+    lse = torch.empty((H, total), dtype=torch.float32, device="cuda")
+    B.s2_attn_fwd_varlen(lay, q, k, v, o, lse, torch.from_numpy(cu).cuda(), w.seqlen, w.scale)
+    torch.cuda.synchronize()
+    assert torch.isfinite(o.float()).all() and torch.isfinite(lse).all()
+    M = orc.block_mask(H, w.num_blocks, w.local_blocks, w.stride)
+    rng = np.random.default_rng(4)
+    for sq, L in enumerate(lens.tolist()):
+        lo = int(cu[sq])
+        rows = sorted({0, S - 1, S, L // 2, (L // S) * S - 1, min((L // S) * S, L - 1), L - 2, L - 1} |
+                      set(int(x) for x in rng.integers(0, L, size=6)))
+        rows = np.array([r for r in rows if 0 <= r < L])
+        for h in (int(rng.integers(0, H)), (5 * sq + 3) % H):
+            f = lambda x: G.bits_f64(x[0, h, lo:lo + L])
+            O, LSE = orc.forward_rows(f(qb)[rows], rows, f(kb), f(vb), M[h], S, w.scale)
+            idx = torch.from_numpy(rows + lo).cuda()
+            assert G.o_excess(G.to_f64(o[0, h][idx]), O) <= 0, (sq, h)
+            assert np.abs(G.to_f64(lse[h][idx]) - LSE).max() <= 1e-3, (sq, h)
