@@ -49,6 +49,34 @@ def test_forward_rows(name, heads, seqlen, chunks):
             assert np.abs(G.to_f64(lc[b, h]) - LSE).max() <= 1e-3
 
 
+@pytest.mark.parametrize("S", [32, 16])
+def test_forward_rows_small_blocks(S):
+    # chunked prefill with 32- and 16-token mask blocks: the same rows as the whole-sequence forward
+    import dataclasses
+    w = dataclasses.replace(synth.WORKLOADS["1p3b_8k"], block_size=S, local_blocks=3, stride=5)
+    H, N = 3, 1024
+    qb, kb, vb, _ = synth.train_inputs(w, heads=H, batch=1, seqlen=N)
+    q, k, v = G.to_dev(qb), G.to_dev(kb), G.to_dev(vb)
+    lay = B.s2_layout_build(B.layout_params(H, N // S, S, w.local_blocks, w.stride))
+    o_full = torch.empty_like(q)
+    lse_full = torch.empty((1, H, N), dtype=torch.float32, device="cuda")
+    B.s2_attn_fwd(lay, q, k, v, o_full, lse_full, w.scale)
+    M = orc.block_mask(H, N // S, w.local_blocks, w.stride)
+    f = G.bits_f64
+    for (r0, n) in [(0, 128), (384, 256), (896, 128)]:
+        qc = q[:, :, r0:r0 + n].contiguous()
+        kc, vc = k[:, :, :r0 + n].contiguous(), v[:, :, :r0 + n].contiguous()
+        oc = torch.empty_like(qc)
+        lc = torch.empty((1, H, n), dtype=torch.float32, device="cuda")
+        B.s2_attn_fwd_rows(lay, qc, kc, vc, oc, lc, r0, w.scale)
+        torch.cuda.synchronize()
+        assert torch.equal(oc, o_full[:, :, r0:r0 + n]) and torch.equal(lc, lse_full[:, :, r0:r0 + n])
+        rows = np.arange(r0, r0 + n)
+        O, LSE = orc.forward_rows(f(qb)[0, 1, rows], rows, f(kb)[0, 1, :r0 + n], f(vb)[0, 1, :r0 + n], M[1], S, w.scale)
+        assert G.o_excess(G.to_f64(oc[0, 1]), O) <= 0
+        assert np.abs(G.to_f64(lc[0, 1]) - LSE).max() <= 1e-3
+
+
 def test_forward_rows_argument_errors():
     w = synth.WORKLOADS["tiny"]
     H, S = 2, w.block_size

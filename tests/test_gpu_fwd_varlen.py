@@ -117,3 +117,32 @@ def test_varlen_length_above_the_stated_maximum_is_cut_there():
             assert np.abs(G.to_f64(lse)[h, lo:lo + L] - LSE).max() <= LSE_TOL
     lo = int(cu[1])
     assert (o.view(torch.int16)[0, :, lo + 200:lo + 300] == SENTINEL).all()
+
+
+def test_varlen_strided_tensors():
+    # q / o and k / v as slices of wider buffers (token stride above head_dim, heads interleaved)
+    w = dataclasses.replace(synth.WORKLOADS["1p3b_8k"], block_size=64, local_blocks=2, stride=3)
+    H, Bk, S, D = 3, 8, 64, 128
+    lens = [200, 17, 512, 90]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    total = int(cu[-1])
+    qb, kb, vb, _ = synth.train_inputs(w, heads=H, batch=1, seqlen=total)
+    lay = B.s2_layout_build(B.layout_params(H, Bk, S, w.local_blocks, w.stride))
+    # [1, total, H, 3*D] buffer: q, k, v of a token side by side, heads next to each other
+    buf = torch.zeros((1, total, H, 3 * D), dtype=torch.bfloat16, device="cuda")
+    buf[..., 0:D] = G.to_dev(qb).permute(0, 2, 1, 3)
+    buf[..., D:2 * D] = G.to_dev(kb).permute(0, 2, 1, 3)
+    buf[..., 2 * D:] = G.to_dev(vb).permute(0, 2, 1, 3)
+    q, k, v = (buf[..., i * D:(i + 1) * D].permute(0, 2, 1, 3) for i in range(3))
+    obuf = torch.zeros((1, total, H, 3 * D), dtype=torch.bfloat16, device="cuda")
+    o = obuf[..., 0:D].permute(0, 2, 1, 3)
+    assert q.stride() == o.stride() and q.stride(2) == 3 * D * H
+    lse = torch.empty((H, total), dtype=torch.float32, device="cuda")
+    B.s2_attn_fwd_varlen(lay, q, k, v, o, lse, torch.from_numpy(cu).cuda(), Bk * S, w.scale)
+    torch.cuda.synchronize()
+    M = orc.block_mask(H, Bk, w.local_blocks, w.stride)
+    f = G.bits_f64
+    O, LSE = orc.attention_forward_varlen(f(qb)[0], f(kb)[0], f(vb)[0], cu, M, S, w.scale)
+    assert G.o_excess(G.to_f64(o.contiguous())[0], O) <= 0
+    assert np.abs(G.to_f64(lse) - LSE).max() <= LSE_TOL
+    assert (obuf[..., D:] == 0).all()   # nothing written outside o's columns

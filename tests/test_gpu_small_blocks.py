@@ -149,3 +149,28 @@ def test_sequences_that_end_inside_a_128_row_tile(S, seqlen):
     assert np.abs(G.to_f64(out["lse"]) - LSE).max() <= LSE_TOL
     for n, ref in (("dq", dQ), ("dk", dK), ("dv", dV)):
         assert G.rel_l2(G.to_f64(out[n]), ref) <= GRAD_TOL, n
+
+
+@pytest.mark.parametrize("S", [32, 16])
+def test_all_blocks_kept_with_small_blocks_is_dense_causal_attention(S):
+    # a layout that keeps every causal block (dense = 1) walked in small blocks must give plain
+    # causal attention, which the library's dense kernel also computes
+    w = dataclasses.replace(synth.WORKLOADS["tiny"], block_size=S)
+    H, N = 2, 384
+    qb, kb, vb, gb = synth.train_inputs(w, heads=H, batch=1, seqlen=N)
+    lay = B.s2_layout_build(B.layout_params(H, N // S, S, 1, 0, dense=1))
+    q, k, v, g = G.to_dev(qb), G.to_dev(kb), G.to_dev(vb), G.to_dev(gb)
+    o = torch.empty_like(q)
+    lse = torch.empty((1, H, N), dtype=torch.float32, device="cuda")
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    ws = torch.empty(B.s2_attn_bwd_workspace_bytes(1, H, N, w.head_dim), dtype=torch.uint8, device="cuda")
+    B.s2_attn_fwd(lay, q, k, v, o, lse, w.scale)
+    B.s2_attn_bwd(lay, q, k, v, o, lse, g, dq, dk, dv, w.scale, ws)
+    torch.cuda.synchronize()
+    M = np.tril(np.ones((H, N // S, N // S), dtype=bool))
+    dQ, dK, dV, O, LSE = orc.attention_backward(G.bits_f64(qb), G.bits_f64(kb), G.bits_f64(vb), G.bits_f64(gb),
+                                                M, S, w.scale)
+    assert G.o_excess(G.to_f64(o), O) <= 0
+    assert np.abs(G.to_f64(lse) - LSE).max() <= LSE_TOL
+    for n, got, ref in (("dq", dq, dQ), ("dk", dk, dK), ("dv", dv, dV)):
+        assert G.rel_l2(G.to_f64(got), ref) <= GRAD_TOL, n

@@ -356,3 +356,19 @@ def test_varlen_forward_argument_errors_without_launch():
     import torch
     if not torch.cuda.is_available():
         assert call(t) == -7                                       # a host-only layout refuses to launch
+
+
+def test_block_count_limits_of_the_tile_lists():
+    # tile-list entries keep the partner index in 15 bits: 32768 blocks, or 65536 16-token ones
+    lib = B.lib()
+    out = C.c_void_p()
+    ok = B.layout_params(1, 32768, 64, 1, 0)
+    assert lib.s2_layout_build(C.byref(ok), C.byref(out)) == 0
+    lib.s2_layout_destroy(out)
+    too_many = B.layout_params(1, 32769, 64, 1, 0)
+    assert lib.s2_layout_build(C.byref(too_many), C.byref(out)) == -8
+    ok16 = B.layout_params(1, 65536, 16, 1, 0)
+    assert lib.s2_layout_build(C.byref(ok16), C.byref(out)) == 0
+    lib.s2_layout_destroy(out)
+    too_many16 = B.layout_params(1, 65538, 16, 1, 0)
+    assert lib.s2_layout_build(C.byref(too_many16), C.byref(out)) == -8
