@@ -428,7 +428,11 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
         for (int kk = 0; kk < D / 16; ++kk) s = mfma32(Tile::row_frag(qs, qt, kk, l32, half), kf[kk], s);
 #pragma unroll
         for (int kk = 0; kk < D / 16; ++kk) dp = mfma32(Tile::row_frag(gs, qt, kk, l32, half), vf[kk], dp);
+        // causal mask: key > qbase + 8g + 4 half + e  <=>  lim > 8g + e, a compare with a constant;
+        // away from the diagonal lim = -1 and nothing is dropped
+        // (the dense instantiation keeps the plain comparison: with this form the compiler spills there)
         const bool diag = qbase < kvw0 + 31;
+        const int lim = diag ? key - qbase - 4 * half : -1;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const int r0 = 32 * qt + 8 * g + 4 * half;
@@ -438,7 +442,7 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
           for (int e = 0; e < 4; ++e) {
             const int r = 4 * g + e;
             float pr = fast_exp2(__builtin_fmaf(s[r], c, -l4[e]));
-            if (diag && key > q0 + r0 + e) pr = 0.f;
+            if (DENSE ? (diag && key > q0 + r0 + e) : (lim > 8 * g + e)) pr = 0.f;
             if (CH == 32 && !((mine >> (g >> 1)) & 1)) pr = 0.f;  // query rows 0..15: block 0, 16..31: block 1
             s[r] = pr;
             dp[r] = pr * (dp[r] - d4[e]);
