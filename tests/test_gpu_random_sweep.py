@@ -68,3 +68,68 @@ def test_random_case(case):
     assert np.abs(G.to_f64(lse) - LSE).max() <= LSE_TOL
     for n, got_t, ref in (("dq", dq, dQ), ("dk", dk, dK), ("dv", dv, dV)):
         assert G.rel_l2(G.to_f64(got_t), ref) <= GRAD_TOL, n
+
+
+def _decode_cases(n, seed=20240718):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        S = int(rng.choice([16, 32, 64, 128]))
+        D = int(rng.choice([64, 128]))
+        H = int(rng.integers(1, 7))
+        nseq = int(rng.integers(1, 6))
+        max_len = int(rng.integers(1, 1500))
+        B_l = int(rng.integers(1, 8))
+        stride = int(rng.choice([0, 1, 2, 3, 5, 8, 11]))
+        base = int(rng.integers(0, 9))
+        window = int(rng.choice([0, 0, 5]))
+        splits = int(rng.choice([0, 1, 2, 5, 16]))
+        paged = bool(rng.integers(0, 2))
+        out.append((S, D, H, nseq, max_len, B_l, stride, base, window, splits, paged))
+    return out
+
+
+@pytest.mark.parametrize("case", _decode_cases(16), ids=lambda c: "S%d_D%d_H%d_n%d_len%d_L%d_V%d_o%d_w%d_sp%d_pg%d" % c)
+def test_random_decode_case(case):
+    S, D, H, nseq, max_len, B_l, stride, base, window, splits, paged = case
+    w = dataclasses.replace(synth.WORKLOADS["tiny" if D == 64 else "7b_decode"], block_size=S, local_blocks=B_l,
+                            stride=stride, window_blocks=window)
+    print("decode sweep case", case, flush=True)
+    rng = np.random.default_rng(sum(case))
+    lens = rng.integers(1, max_len + 1, size=nseq).astype(np.int32)
+    lens[0] = max_len
+    qb, kcb, vcb, lens = synth.decode_inputs_small(w, nseq, H, max_len, lengths=lens)
+    params = B.layout_params(H, 1, S, B_l, stride, base, window, 0)
+    q = G.to_dev(qb)
+    sl = torch.from_numpy(lens).cuda()
+    o = torch.empty_like(q)
+    lse = torch.empty((nseq, H), dtype=torch.float32, device="cuda")
+    max_blocks = -(-max_len // S)
+    ws = torch.empty(B.s2_attn_decode_workspace_bytes(nseq, H, D, max_blocks * S, splits), dtype=torch.uint8,
+                     device="cuda")
+    f = G.bits_f64
+    if paged:
+        resident = [[B.s2_kv_resident_blocks(params, h, int(L)) for h in range(H)] for L in lens]
+        for b, L in enumerate(lens):
+            for h in range(H):
+                assert resident[b][h] == orc.resident_blocks(int(L), base + h, S, B_l, stride, window)
+        table, num_pages = synth.page_table(resident, max_blocks, index=w.index)
+        pad = max_blocks * S - max_len
+        kcb = np.concatenate([kcb, np.zeros((nseq, H, pad, D), np.uint16)], axis=2)
+        vcb = np.concatenate([vcb, np.zeros((nseq, H, pad, D), np.uint16)], axis=2)
+        kpool = synth.pages_from_cache(kcb, table, num_pages, S)
+        vpool = synth.pages_from_cache(vcb, table, num_pages, S)
+        missing = torch.zeros(1, dtype=torch.int32, device="cuda")
+        B.s2_attn_decode_paged(params, q, G.to_dev(kpool), G.to_dev(vpool), torch.from_numpy(table).cuda(), sl, o,
+                               lse, w.scale, ws, missing=missing, num_splits=splits)
+        torch.cuda.synchronize()
+        assert int(missing.item()) == 0
+    else:
+        B.s2_attn_decode(params, q, G.to_dev(kcb), G.to_dev(vcb), sl, o, lse, w.scale, ws, max_len, num_splits=splits)
+        torch.cuda.synchronize()
+    for b in range(nseq):
+        for h in range(H):
+            ref, ref_lse = orc.decode_row(f(qb)[b, h], f(kcb)[b, h], f(vcb)[b, h], int(lens[b]), base + h, S, B_l,
+                                          stride, w.scale, window)
+            assert G.o_excess(G.to_f64(o[b, h]), ref) <= 0, (b, h)
+            assert abs(float(lse[b, h]) - ref_lse) <= LSE_TOL, (b, h)
