@@ -130,15 +130,18 @@ def bench_train(w, steps, warmup, with_dense=True, with_bwd=True, dense_steps=3,
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     t_wall = time.perf_counter()
-    e0.record()
-    for _ in range(steps):
+    marks[0].record()
+    for i in range(steps):
         step()
-    e1.record()
+        marks[i + 1].record()   # an event between steps costs nothing on the stream; gives median and min
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t_wall) * 1e3 / steps
-    ms_step = e0.elapsed_time(e1) / steps
+    ms_step = marks[0].elapsed_time(marks[steps]) / steps
+    each = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
+    res["ms_step_median"] = each[len(each) // 2]
+    res["ms_step_min"] = each[0]
 
     res["ms_per_step"] = ms_step
     res["wall_ms_per_step"] = wall_ms
