@@ -71,7 +71,8 @@ def test_7b_32k_full():
     out = G.run_fwd_bwd(w, *bits)
     rng = np.random.default_rng(2)
     _check_forward_rows(w, out["o"], out["lse"], bits[:3], [(0, h) for h in (0, 5, 15, 16, 31)], rng)
-    _check_backward_head(w, out, bits, 0, 21)
+    for h in (0, 21, 31):   # smallest and largest stripe offsets and one between; about ten seconds of oracle each
+        _check_backward_head(w, out, bits, 0, h)
     for n in ("o", "dq", "dk", "dv"):
         assert torch.isfinite(out[n].float()).all()
 
