@@ -7,6 +7,7 @@ import pytest
 import torch
 
 from oracle import s2_oracle as orc
+from paper_2407_17678_amd import binding as B
 from paper_2407_17678_amd import synth
 from tests import gpu_util as G
 
@@ -100,3 +101,43 @@ def test_strided_tensors_backward():
     assert G.o_excess(G.to_f64(o), O) <= 0
     for n, got, ref in (("dq", dq, dQ), ("dk", dk, dK), ("dv", dv, dV)):
         assert G.rel_l2(G.to_f64(got), ref) <= GRAD_TOL, n
+
+
+def test_one_layout_on_two_streams_at_once():
+    # a layout handle is immutable: forward + backward of two different batches, issued on two
+    # streams without waiting for each other, must equal the same calls made one after the other
+    # (each call has its own tensors and workspace; nothing in the library is shared between calls)
+    w = synth.WORKLOADS["1p3b_8k"]
+    H, N, S, D = 4, 2048, w.block_size, w.head_dim
+    lay = B.s2_layout_build(B.layout_params(H, N // S, S, w.local_blocks, w.stride))
+    sets = []
+    for i in range(2):
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(100 + i)
+        q, k, v, g = (torch.randn((2, H, N, D), device="cuda", generator=gen).to(torch.bfloat16) for _ in range(4))
+        bufs = dict(o=torch.empty_like(q), lse=torch.empty((2, H, N), dtype=torch.float32, device="cuda"),
+                    dq=torch.empty_like(q), dk=torch.empty_like(q), dv=torch.empty_like(q),
+                    ws=torch.empty(B.s2_attn_bwd_workspace_bytes(2, H, N, D), dtype=torch.uint8, device="cuda"))
+        sets.append((q, k, v, g, bufs))
+
+    def run(i, stream):
+        q, k, v, g, b = sets[i]
+        B.s2_attn_fwd(lay, q, k, v, b["o"], b["lse"], w.scale, stream=stream)
+        B.s2_attn_bwd(lay, q, k, v, b["o"], b["lse"], g, b["dq"], b["dk"], b["dv"], w.scale, b["ws"], stream=stream)
+
+    for i in range(2):
+        run(i, None)
+    torch.cuda.synchronize()
+    serial = [{n: sets[i][4][n].clone() for n in ("o", "lse", "dq", "dk", "dv")} for i in range(2)]
+    for i in range(2):
+        for n in ("o", "lse", "dq", "dk", "dv"):
+            sets[i][4][n].zero_()
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(3):
+        for i in range(2):
+            run(i, streams[i])
+    torch.cuda.synchronize()
+    for i in range(2):
+        for n in ("o", "lse", "dq", "dk", "dv"):
+            assert torch.equal(sets[i][4][n], serial[i][n]), (i, n)
