@@ -229,7 +229,9 @@ int s2_attn_decode(const s2_layout_params* p, const s2_decode_args* a, float sca
                    void* workspace, size_t workspace_bytes, void* stream);
 size_t s2_attn_decode_workspace_bytes(int32_t nseq, int32_t heads, int32_t head_dim,
                                       int32_t max_len, int32_t num_splits);
-/* The split count the library would pick for num_splits == 0. */
+/* Upper bound on the split count the library picks for num_splits == 0, and the count that
+ * s2_attn_decode_workspace_bytes(..., 0) sizes the workspace for.  The call itself may use fewer
+ * splits when the pattern keeps so few blocks per row that more splits would leave wavefronts idle. */
 int32_t s2_attn_decode_default_splits(int32_t nseq, int32_t heads, int32_t max_len);
 
 /* Same step against a paged cache.  A kept block whose table entry is negative (or not below

@@ -400,6 +400,20 @@ int check_pattern(const s2_layout_params* lp, const s2_layout* layout, int heads
   return S2_OK;
 }
 
+// Split count when the caller leaves it to the library: the public default (enough workgroups to
+// fill the chip; it also sizes the workspace, so never more than that), cut down so that a
+// workgroup still has about a dozen 64-token units of the longest row to walk: with fewer, its four
+// wavefronts mostly idle and the reduce kernel merges partials for nothing.
+int choose_splits(const s2_layout_params* lp, const s2_layout* layout, int nseq, int heads, int max_len) {
+  int splits = s2_attn_decode_default_splits(nseq, heads, max_len);
+  const int S = lp->block_size;
+  int64_t blocks = layout ? layout->max_row_blocks : s2::row_blocks(*lp, 0, (max_len - 1) / S, nullptr, 0);
+  const int64_t units = blocks * S / 64;  // 64-token units of work in the longest row
+  const int64_t cap = units / 12 < 1 ? 1 : units / 12;
+  if (splits > cap) splits = (int)cap;
+  return splits;
+}
+
 void set_pattern(s2::DecodeParams& p, const s2_layout_params* lp, const s2_layout* layout) {
   p.block_size = lp->block_size;
   p.local_blocks = lp->local_blocks;
@@ -430,8 +444,7 @@ int decode_contiguous(const s2_layout_params* lp, const s2_layout* layout, const
   if (!aligned16(a->q) || !aligned16(a->k_cache) || !aligned16(a->v_cache) || !aligned16(a->o) ||
       (reinterpret_cast<uintptr_t>(a->seq_lens) & 3u) != 0)
     return S2_ERR_ALIGN;
-  const int splits = a->num_splits > 0 ? a->num_splits
-                                       : s2_attn_decode_default_splits(a->nseq, a->heads, a->max_len);
+  const int splits = a->num_splits > 0 ? a->num_splits : choose_splits(lp, layout, a->nseq, a->heads, a->max_len);
   const size_t need = s2_attn_decode_workspace_bytes(a->nseq, a->heads, a->head_dim, a->max_len, splits);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || workspace_bytes < need)
     return S2_ERR_WORKSPACE;
@@ -480,8 +493,7 @@ int decode_paged(const s2_layout_params* lp, const s2_layout* layout, const s2_p
       (reinterpret_cast<uintptr_t>(a->block_table) & 3u) != 0 ||
       (reinterpret_cast<uintptr_t>(a->missing) & 3u) != 0)
     return S2_ERR_ALIGN;
-  const int splits = a->num_splits > 0 ? a->num_splits
-                                       : s2_attn_decode_default_splits(a->nseq, a->heads, max_len);
+  const int splits = a->num_splits > 0 ? a->num_splits : choose_splits(lp, layout, a->nseq, a->heads, max_len);
   const size_t need = s2_attn_decode_workspace_bytes(a->nseq, a->heads, a->head_dim, max_len, splits);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || workspace_bytes < need)
     return S2_ERR_WORKSPACE;
