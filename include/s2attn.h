@@ -8,6 +8,13 @@
  * in (a hipStream_t cast to void*, NULL = the default stream); no call synchronises
  * the device except s2_layout_build/destroy (one upload / free of small arrays).
  *
+ * Threads, streams, graphs: the library keeps no mutable state between calls apart from a
+ * per-thread copy of the last HIP error.  A layout handle is read-only after it is built and may
+ * drive any number of threads and streams at once; two calls may run concurrently whenever their
+ * outputs and workspaces do not overlap.  The compute calls only enqueue kernels (no allocation,
+ * no memset, no host synchronisation), so they may be captured into a HIP graph once each kernel
+ * has been launched at least once outside a capture.
+ *
  * Every function returns an int status: S2_OK (0) or a negative S2_ERR_* code.
  * Arguments are validated before anything is launched; on error no output is
  * written.  No C++ exception crosses this boundary.
