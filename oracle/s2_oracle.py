@@ -24,8 +24,9 @@ What each function follows:
   plus causality inside the diagonal block.
 * ``attention_forward`` / ``attention_backward`` - softmax attention over the
   kept keys only (section 3.2) and its analytic gradient.
-* ``attention_forward_varlen`` - the forward on a packed batch of sequences of
-  different lengths, each an independent problem (serving prefill, section 5.3).
+* ``attention_forward_varlen`` / ``attention_backward_varlen`` - forward and
+  gradients on a packed batch of sequences of different lengths, each an
+  independent problem (serving prefill, section 5.3; packed training batches).
 * ``decode_row`` - one decoding step against a cache (section 4.1): the last
   row of the same masked attention.
 * ``resident_blocks`` / ``paged_decode_row`` - section 4.1's KV-efficient
@@ -321,6 +322,29 @@ def attention_forward_varlen(q, k, v, cu_seqlens, M, block_size, scale):
             O[h, lo:hi], LSE[h, lo:hi] = attention_forward_head(q[h, lo:hi], k[h, lo:hi], v[h, lo:hi], M[h],
                                                                 block_size, scale)
     return O, LSE
+
+
+def attention_backward_varlen(q, k, v, dO, cu_seqlens, M, block_size, scale):
+    """Gradients of sum(O*dO) for a packed batch (see attention_forward_varlen).
+
+    Every sequence is differentiated on its own.  Returns (dQ, dK, dV, O, LSE) in
+    the packed shapes; rows that belong to no sequence come back as NaN.
+    """
+    q, k, v, dO = np.asarray(q), np.asarray(k), np.asarray(v), np.asarray(dO)
+    H, total, _ = q.shape
+    cu = [int(x) for x in cu_seqlens]
+    dQ = np.full(q.shape, np.nan, dtype=np.float64)
+    dK = np.full(k.shape, np.nan, dtype=np.float64)
+    dV = np.full(v.shape, np.nan, dtype=np.float64)
+    O = np.full(v.shape, np.nan, dtype=np.float64)
+    LSE = np.full((H, total), np.nan, dtype=np.float64)
+    for lo, hi in zip(cu[:-1], cu[1:]):
+        if hi == lo:
+            continue
+        for h in range(H):
+            dQ[h, lo:hi], dK[h, lo:hi], dV[h, lo:hi], O[h, lo:hi], LSE[h, lo:hi] = attention_backward_head(
+                q[h, lo:hi], k[h, lo:hi], v[h, lo:hi], dO[h, lo:hi], M[h], block_size, scale)
+    return dQ, dK, dV, O, LSE
 
 
 def forward_rows(q_rows, row_index, k, v, Mh, block_size, scale):
