@@ -342,8 +342,16 @@ def bench_prefill_varlen(w, steps, warmup, nseq=12, min_len=1024):
     lsep = torch.empty((nseq, H, pad_len), dtype=torch.float32, device="cuda")
     run_p = lambda: B.s2_attn_fwd(lay_p, qp, kp, vp, op, lsep, w.scale)
     ms_pad = time_events(run_p, max(3, steps // 2), 2)
+    # the same packed batch as a training step: forward + backward in two more launches
+    g = torch.randn((1, H, total, D), device="cuda", generator=gen).to(torch.bfloat16)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+    wsb = torch.empty(B.s2_attn_bwd_varlen_workspace_bytes(H, total, D), dtype=torch.uint8, device="cuda")
+    run_b = lambda: B.s2_attn_bwd_varlen(lay, q, k, v, o, lse, g, dq, dk, dv, cud, w.seqlen, w.scale, wsb)
+    run()
+    ms_bwd = time_events(run_b, steps, warmup)
     tf = 4.0 * D * pairs / (ms * 1e-3) / 1e12
-    return dict(workload=w.name + "_prefill_varlen", nseq=nseq, heads=H, head_dim=D, block_size=S,
+    extra_bwd = dict(ms_bwd=ms_bwd, tflops_fwd_bwd=14.0 * D * pairs / ((ms + ms_bwd) * 1e-3) / 1e12)
+    return dict(extra_bwd, workload=w.name + "_prefill_varlen", nseq=nseq, heads=H, head_dim=D, block_size=S,
                 lengths=lens.tolist(), total_tokens=total, ms=ms, unmasked_pairs=pairs, tflops=tf,
                 pct_mfma_peak=100.0 * tf / PEAK_BF16_TFLOPS, ms_padded_to_longest=ms_pad,
                 speedup_vs_padded=ms_pad / ms)

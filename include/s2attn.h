@@ -206,6 +206,16 @@ int s2_attn_bwd(const s2_layout* layout, const s2_tensors* t, float scale, void*
                 size_t workspace_bytes, void* stream);
 size_t s2_attn_bwd_workspace_bytes(int32_t batch, int32_t heads, int32_t seqlen, int32_t head_dim);
 
+/* The backward for a packed batch of sequences of different lengths: the gradient of
+ * s2_attn_fwd_varlen, same tensors and cu_seqlens (o and lse as that call left them), d_o / dq /
+ * dk / dv packed like q / k / v.  Rows that belong to no sequence are left as they were.
+ * workspace: s2_attn_bwd_varlen_workspace_bytes(heads, rows of the tensors, head_dim) bytes,
+ * DEVICE, 256-byte aligned.  Errors as s2_attn_fwd_varlen plus WORKSPACE. */
+int s2_attn_bwd_varlen(const s2_layout* layout, const s2_tensors* t, const int32_t* cu_seqlens,
+                       int32_t num_seqs, int32_t max_seqlen, float scale, void* workspace,
+                       size_t workspace_bytes, void* stream);
+size_t s2_attn_bwd_varlen_workspace_bytes(int32_t heads, int32_t rows, int32_t head_dim);
+
 /* The backward is two launches: dQ (which also computes delta = rowsum(dO*O) and leaves it in
  * the workspace), then dK/dV (which reads delta).  This variant runs the subset named by `stages`
  * (an OR of the flags below) so that a profiler or a benchmark can time each launch on its own;

@@ -73,7 +73,8 @@ class PagedDecodeArgs(C.Structure):
 
 
 EXPORTS = (
-    "s2_layout_build", "s2_layout_from_csr", "s2_layout_destroy", "s2_layout_get", "s2_attn_fwd", "s2_attn_fwd_rows", "s2_attn_fwd_varlen", "s2_attn_bwd",
+    "s2_layout_build", "s2_layout_from_csr", "s2_layout_destroy", "s2_layout_get", "s2_attn_fwd", "s2_attn_fwd_rows", "s2_attn_fwd_varlen", "s2_attn_bwd_varlen",
+    "s2_attn_bwd_varlen_workspace_bytes", "s2_attn_bwd",
     "s2_attn_bwd_workspace_bytes", "s2_attn_bwd_stages", "s2_dense_causal_fwd", "s2_dense_causal_bwd", "s2_attn_decode",
     "s2_attn_decode_workspace_bytes", "s2_attn_decode_default_splits", "s2_attn_decode_paged",
     "s2_kv_resident_blocks", "s2_attn_decode_layout", "s2_attn_decode_paged_layout",
@@ -101,6 +102,10 @@ def lib():
     L.s2_attn_fwd_rows.argtypes = [C.c_void_p, C.POINTER(Tensors), C.c_int32, C.c_int32, C.c_float, C.c_void_p]
     L.s2_attn_fwd_varlen.argtypes = [C.c_void_p, C.POINTER(Tensors), C.c_void_p, C.c_int32, C.c_int32, C.c_float,
                                      C.c_void_p]
+    L.s2_attn_bwd_varlen.argtypes = [C.c_void_p, C.POINTER(Tensors), C.c_void_p, C.c_int32, C.c_int32, C.c_float,
+                                     C.c_void_p, C.c_size_t, C.c_void_p]
+    L.s2_attn_bwd_varlen_workspace_bytes.argtypes = [C.c_int32] * 3
+    L.s2_attn_bwd_varlen_workspace_bytes.restype = C.c_size_t
     L.s2_attn_bwd.argtypes = [C.c_void_p, C.POINTER(Tensors), C.c_float, C.c_void_p, C.c_size_t, C.c_void_p]
     L.s2_attn_bwd_stages.argtypes = [C.c_void_p, C.POINTER(Tensors), C.c_float, C.c_void_p, C.c_size_t,
                                      C.c_int, C.c_void_p]
@@ -247,6 +252,19 @@ def s2_attn_fwd_varlen(layout, q, k, v, o, lse, cu_seqlens, max_seqlen, scale, s
     assert q.shape[0] == 1 and cu_seqlens.is_contiguous() and cu_seqlens.numel() >= 2
     _check(lib().s2_attn_fwd_varlen(layout.handle, C.byref(t), _ptr(cu_seqlens), cu_seqlens.numel() - 1,
                                     max_seqlen, scale, _stream_ptr(stream)), "s2_attn_fwd_varlen")
+
+
+def s2_attn_bwd_varlen_workspace_bytes(heads, rows, head_dim):
+    return lib().s2_attn_bwd_varlen_workspace_bytes(heads, rows, head_dim)
+
+
+def s2_attn_bwd_varlen(layout, q, k, v, o, lse, d_o, dq, dk, dv, cu_seqlens, max_seqlen, scale, workspace, stream=None):
+    """Gradient of s2_attn_fwd_varlen; d_o, dq, dk, dv packed like q."""
+    t = _tensors(q, k, v, o, lse, d_o, dq, dk, dv)
+    assert q.shape[0] == 1 and cu_seqlens.is_contiguous() and cu_seqlens.numel() >= 2
+    _check(lib().s2_attn_bwd_varlen(layout.handle, C.byref(t), _ptr(cu_seqlens), cu_seqlens.numel() - 1, max_seqlen,
+                                    scale, _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                    _stream_ptr(stream)), "s2_attn_bwd_varlen")
 
 
 def s2_attn_bwd_workspace_bytes(batch, heads, seqlen, head_dim):

@@ -2,6 +2,7 @@
 // the kernels.  See include/s2attn.h for the contract of every entry point.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <limits>
@@ -301,6 +302,46 @@ int s2_attn_fwd_varlen(const s2_layout* layout, const s2_tensors* t, const int32
   const int64_t slots = 8 * (((int64_t)num_seqs * t->heads + 7) / 8) * ((max_seqlen + s2::kFwdBM - 1) / s2::kFwdBM);
   if (slots > std::numeric_limits<int32_t>::max()) return S2_ERR_SHAPE;
   return hip_ok(s2::launch_fwd(p, false, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
+}
+
+size_t s2_attn_bwd_varlen_workspace_bytes(int32_t heads, int32_t rows, int32_t head_dim) {
+  (void)head_dim;
+  if (heads < 1 || rows < 1) return 0;
+  // delta and base-2 LSE per (head, row), plus one chunk of slack each: the dK/dV kernel fetches the
+  // statistics of a whole 64-row chunk even where a sequence ends inside it
+  const size_t floats = (size_t)heads * rows + 64;
+  return 2 * (((floats * sizeof(float) + 255) / 256) * 256);
+}
+
+int s2_attn_bwd_varlen(const s2_layout* layout, const s2_tensors* t, const int32_t* cu_seqlens,
+                       int32_t num_seqs, int32_t max_seqlen, float scale, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+  if (!layout || !cu_seqlens) return S2_ERR_NULL;
+  int st = check_tensors(t, true, scale);
+  if (st != S2_OK) return st;
+  if (t->batch != 1 || t->heads != layout->p.num_heads) return S2_ERR_SHAPE;
+  if (num_seqs < 1 || max_seqlen < 1) return S2_ERR_SHAPE;
+  if ((int64_t)max_seqlen > (int64_t)layout->p.num_blocks * layout->p.block_size) return S2_ERR_SHAPE;
+  if ((reinterpret_cast<uintptr_t>(cu_seqlens) & 3u) != 0) return S2_ERR_ALIGN;
+  const size_t need = s2_attn_bwd_varlen_workspace_bytes(t->heads, t->seqlen, t->head_dim);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || workspace_bytes < need)
+    return S2_ERR_WORKSPACE;
+  if (!layout_on_current_device(layout)) return S2_ERR_NO_DEVICE;
+  s2::AttnParams p = make_params(t, scale);
+  p.batch = num_seqs;
+  p.q_rows = max_seqlen;
+  p.cu_seqlens = cu_seqlens;
+  p.block_size = layout->p.block_size;
+  p.fwd_tiles = dev_tiles(layout->fwd_tiles);
+  p.q_tiles = dev_tiles(layout->q_tiles);
+  p.kv_tiles = dev_tiles(layout->kv_tiles);
+  p.delta = static_cast<float*>(workspace);
+  p.lse2 = p.delta + need / 8;
+  // one grid slot per (sequence, head, tile): query tiles of the longest length allowed, key tiles of the layout
+  const int64_t pairs = 8 * (((int64_t)num_seqs * t->heads + 7) / 8);
+  const int64_t slots = pairs * std::max<int64_t>((max_seqlen + s2::kBwdBM - 1) / s2::kBwdBM, layout->kv_tiles.tiles_per_head);
+  if (slots > std::numeric_limits<int32_t>::max()) return S2_ERR_SHAPE;
+  return hip_ok(s2::launch_bwd(p, false, s2::kBwdAll, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
 }
 
 int s2_attn_bwd_stages(const s2_layout* layout, const s2_tensors* t, float scale, void* workspace,

@@ -69,7 +69,10 @@ struct DqSmem {
   uint16_t v[2][DmaTile<D, CH>::kElems];
 };
 
-template <int D, bool DENSE, int CH>
+// VARLEN: a packed batch of sequences of different lengths (see the forward kernel): the workgroup
+// finds its sequence in cu_seqlens; loads that would pass the sequence's last token are clamped to
+// it (keys there lie after every query, which the causal mask drops) and stores are guarded per lane.
+template <int D, bool DENSE, int CH, bool VARLEN = false>
 __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
   typedef DmaTile<D, CH> Tile;
   constexpr int KT = CH / 32;
@@ -80,10 +83,20 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63, l32 = lane & 31, half = lane >> 5;
   const int T = p.q_tiles.tiles_per_head;
+  const int T_run = VARLEN ? (p.q_rows + kBwdBM - 1) / kBwdBM : T;
   int bh, rank;
-  if (!map_workgroup(blockIdx.x, p.batch * p.heads, T, bh, rank)) return;
+  if (!map_workgroup(blockIdx.x, p.batch * p.heads, T_run, bh, rank)) return;
   const int b = bh / p.heads, h = bh - b * p.heads;
-  const int tile = DENSE ? (T - 1 - rank) : p.q_tiles.order[h * T + rank];
+  int tile = DENSE ? (T - 1 - rank) : VARLEN ? 0 : p.q_tiles.order[h * T + rank];
+  int row_base = 0, N = p.seqlen;
+  if (VARLEN) {
+    const int lo = p.cu_seqlens[b], hi = p.cu_seqlens[b + 1];
+    row_base = min(max(lo, 0), p.seqlen);  // whatever the array holds, stay inside the tensors
+    N = min(min(max(hi - lo, 0), p.q_rows), p.seqlen - row_base);
+    const int T_seq = (N + kBwdBM - 1) / kBwdBM;
+    if (rank >= T_seq) return;
+    tile = T_seq - 1 - rank;
+  }
   const int S = DENSE ? kChunk : p.block_size;
   // 16-token blocks: a list entry is a unit of two blocks (32 keys, one step) and my 32 query rows
   // are two mask rows, so which keys a lane may see is a 2 x 2 pattern of bits per wavefront
@@ -91,13 +104,12 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
   const int Sg = fine ? 32 : S;  // tokens per list entry
   const int cpb = Sg / CH;  // a power of two: / and % below are a shift and a mask
   const int cpb_sh = __builtin_ctz(cpb), cpb_m = cpb - 1;
-  const int N = p.seqlen;
   const int qw0 = tile * kBwdBM + wave * 32;
   const bool wave_active = qw0 < N;
   const int my_member = (qw0 / Sg) - tile * (kBwdBM / Sg);
 
-  const int64_t q_off = b * p.q_sb + h * p.q_sh;
-  const int64_t kv_off = b * p.kv_sb + h * p.kv_sh;
+  const int64_t q_off = (VARLEN ? row_base * p.q_st : b * p.q_sb) + h * p.q_sh;
+  const int64_t kv_off = (VARLEN ? row_base * p.kv_st : b * p.kv_sb) + h * p.kv_sh;
   const uint16_t* kb = p.k + kv_off;
   const uint16_t* vb = p.v + kv_off;
 
@@ -145,8 +157,14 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
     int kv0, pat;
     bool keep;
     chunk_of(0, kv0, keep, pat);
-    Tile::issue(plan, kb + (int64_t)kv0 * p.kv_st, sm.k[0], wave);
-    Tile::issue(plan, vb + (int64_t)kv0 * p.kv_st, sm.v[0], wave);
+    if (VARLEN && kv0 + CH > N) {
+      const typename Tile::Plan pr = Tile::plan_rows(p.kv_st, wave, lane, N - kv0);
+      Tile::issue(pr, kb + (int64_t)min(kv0, N - 1) * p.kv_st, sm.k[0], wave);
+      Tile::issue(pr, vb + (int64_t)min(kv0, N - 1) * p.kv_st, sm.v[0], wave);
+    } else {
+      Tile::issue(plan, kb + (int64_t)kv0 * p.kv_st, sm.k[0], wave);
+      Tile::issue(plan, vb + (int64_t)kv0 * p.kv_st, sm.v[0], wave);
+    }
   }
 
   bf16x8 qf[D / 16], gf[D / 16];  // Q^T and dO^T fragments (B operands), lane = query
@@ -156,10 +174,13 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
   // needs no separate pass over O and dO; it is also written out, with LSE in base-2 units, for
   // the dK/dV kernel, which runs after this one.
   float part = 0.f;
+  // my query's row; a lane past the ragged end of a packed sequence reads the last row (never stored)
+  const int my_row = VARLEN ? min(qw0 + l32, N - 1) : qw0 + l32;
+  const bool my_row_exists = !VARLEN || qw0 + l32 < N;
 #pragma unroll
   for (int kk = 0; kk < D / 16; ++kk) {
     if (wave_active) {
-      const int64_t o = q_off + (int64_t)(qw0 + l32) * p.q_st + 16 * kk + 8 * half;
+      const int64_t o = q_off + (int64_t)my_row * p.q_st + 16 * kk + 8 * half;
       qf[kk] = *reinterpret_cast<const bf16x8*>(p.q + o);
       gf[kk] = *reinterpret_cast<const bf16x8*>(p.d_o + o);
       const bf16x8 of = *reinterpret_cast<const bf16x8*>(p.o + o);
@@ -172,9 +193,10 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
   }
   delta_l = sum_halves(part);
   if (wave_active) {
-    const int64_t r = ((int64_t)b * p.heads + h) * N + qw0 + l32;
+    const int64_t r = VARLEN ? (int64_t)h * p.seqlen + row_base + my_row  // [heads, rows of the tensors]
+                             : ((int64_t)b * p.heads + h) * N + my_row;
     lse_l = p.lse[r] * kLog2e;
-    if (half == 0) {
+    if (half == 0 && my_row_exists) {
       p.delta[r] = delta_l;
       p.lse2[r] = lse_l;
     }
@@ -196,8 +218,14 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
     if (it + 1 < total) {
       int kv1;
       next_chunk_of(it, kv1);
-      Tile::issue(plan, kb + (int64_t)kv1 * p.kv_st, sm.k[buf ^ 1], wave);
-      Tile::issue(plan, vb + (int64_t)kv1 * p.kv_st, sm.v[buf ^ 1], wave);
+      if (VARLEN && kv1 + CH > N) {
+        const typename Tile::Plan pr = Tile::plan_rows(p.kv_st, wave, lane, N - kv1);
+        Tile::issue(pr, kb + (int64_t)min(kv1, N - 1) * p.kv_st, sm.k[buf ^ 1], wave);
+        Tile::issue(pr, vb + (int64_t)min(kv1, N - 1) * p.kv_st, sm.v[buf ^ 1], wave);
+      } else {
+        Tile::issue(plan, kb + (int64_t)kv1 * p.kv_st, sm.k[buf ^ 1], wave);
+        Tile::issue(plan, vb + (int64_t)kv1 * p.kv_st, sm.v[buf ^ 1], wave);
+      }
     }
 
     if (wave_active && keep && kv0 <= qw0 + 31) {
@@ -246,7 +274,7 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
     __syncthreads();
   }
 
-  if (!wave_active) return;
+  if (!wave_active || !my_row_exists) return;
   uint16_t* row = p.dq + q_off + (int64_t)(qw0 + l32) * p.q_st;
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt)
@@ -271,7 +299,11 @@ struct DkvSmem {
   } rs[2];                 // one 512-byte direct load fills both arrays of a stage
 };
 
-template <int D, bool DENSE, int CH>
+// VARLEN: a packed batch of sequences of different lengths.  A key tile's members are columns of
+// the whole layout, so the workgroup first drops out if none of them exists in its sequence, skips
+// the list entries (query blocks, last first) that lie after the sequence's end, clamps the loads
+// of the ragged last chunk and zeroes P and dS for the query rows of it that do not exist.
+template <int D, bool DENSE, int CH, bool VARLEN = false>
 __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
   typedef DmaTile<D, CH> Tile;
   constexpr int QT = CH / 32;
@@ -293,7 +325,12 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
   const int Sg = fine ? 32 : S;  // tokens per list entry
   const int cpb = Sg / CH;  // a power of two: / and % below are a shift and a mask
   const int cpb_sh = __builtin_ctz(cpb), cpb_m = cpb - 1;
-  const int N = p.seqlen;
+  int row_base = 0, N = p.seqlen;
+  if (VARLEN) {
+    const int lo = p.cu_seqlens[b], hi = p.cu_seqlens[b + 1];
+    row_base = min(max(lo, 0), p.seqlen);  // whatever the array holds, stay inside the tensors
+    N = min(min(max(hi - lo, 0), p.q_rows), p.seqlen - row_base);
+  }
 
   // my 32 key rows
   int kvw0, my_member = 0;
@@ -303,17 +340,25 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
     wave_active = kvw0 < N;
   } else {
     my_member = (wave * 32) / S;  // with 16-token blocks the first of my two (adjacent) columns
-    const int blk = p.kv_tiles.members[(h * T + tile) * p.kv_tiles.group + my_member];
-    wave_active = blk >= 0;
+    const int32_t* mem = p.kv_tiles.members + (h * T + tile) * p.kv_tiles.group;
+    if (VARLEN) {  // the whole workgroup leaves together when none of its columns is in the sequence
+      bool any = false;
+      for (int m = 0; m < p.kv_tiles.group; ++m) any = any || (mem[m] >= 0 && mem[m] * S < N);
+      if (!any) return;
+    }
+    const int blk = mem[my_member];
     kvw0 = blk * S + (wave * 32) % S;
+    wave_active = blk >= 0 && kvw0 < N;
   }
 
-  const int64_t q_off = b * p.q_sb + h * p.q_sh;
-  const int64_t kv_off = b * p.kv_sb + h * p.kv_sh;
+  const int64_t q_off = (VARLEN ? row_base * p.q_st : b * p.q_sb) + h * p.q_sh;
+  const int64_t kv_off = (VARLEN ? row_base * p.kv_st : b * p.kv_sb) + h * p.kv_sh;
   const uint16_t* qb = p.q + q_off;
   const uint16_t* gb = p.d_o + q_off;
-  const float* lse_b = p.lse2 + ((int64_t)b * p.heads + h) * N;
-  const float* delta_b = p.delta + ((int64_t)b * p.heads + h) * N;
+  // packed batch: the row statistics are [heads, rows of the tensors]
+  const int64_t stats_off = VARLEN ? (int64_t)h * p.seqlen + row_base : ((int64_t)b * p.heads + h) * N;
+  const float* lse_b = p.lse2 + stats_off;
+  const float* delta_b = p.delta + stats_off;
 
   int ent_lo = 0, n_ent;
   if (DENSE) {
@@ -360,26 +405,43 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
   // registers across the loop: this kernel has no registers to spare, and a spilled constant costs
   // a wait for all outstanding loads when it is fetched back.
   auto issue_chunk = [&](int q0, int buf, int ln) {
-    Tile::issue(plan, qb + (int64_t)q0 * p.q_st, sm.q[buf], wave);
-    Tile::issue(plan, gb + (int64_t)q0 * p.q_st, sm.g[buf], wave);
+    if (VARLEN && q0 + CH > N) {  // ragged end of the sequence: rows past it fetch its last row instead
+      const typename Tile::Plan pr = Tile::plan_rows(p.q_st, wave, ln, N - q0);
+      Tile::issue(pr, qb + (int64_t)q0 * p.q_st, sm.q[buf], wave);
+      Tile::issue(pr, gb + (int64_t)q0 * p.q_st, sm.g[buf], wave);
+    } else {
+      Tile::issue(plan, qb + (int64_t)q0 * p.q_st, sm.q[buf], wave);
+      Tile::issue(plan, gb + (int64_t)q0 * p.q_st, sm.g[buf], wave);
+    }
     // CH floats of each array: the first CH/4 lanes fetch delta, the next CH/4 lanes lse, 16 bytes
     // each, in one direct load issued by the wavefront that has one load fewer than the others in the two tiles
     constexpr int NL = CH / 4;  // lanes per array, 16 bytes each
     if (wave == 3 && ln < 2 * NL)
       dma16(delta_b + q0, 16 * ln + (ln < NL ? 0u : stats_gap - 16u * NL), lds_addr(&sm.rs[buf]));
   };
-  if (total > 0) {
+  // first step: a packed sequence skips the chunks of query blocks that lie after its end (the list
+  // starts at the layout's last row)
+  int it0 = 0;
+  if (VARLEN) {
+    for (; it0 < total; ++it0) {
+      int q0, pat;
+      bool keep;
+      chunk_of(it0, q0, keep, pat);
+      if (q0 < N) break;
+    }
+  }
+  if (it0 < total) {
     int q0, pat;
     bool keep;
-    chunk_of(0, q0, keep, pat);
-    issue_chunk(q0, 0, lane);
+    chunk_of(it0, q0, keep, pat);
+    issue_chunk(q0, it0 & 1, lane);
   }
 
   bf16x8 kf[D / 16], vf[D / 16];  // K and V fragments (B operands), lane = key
 #pragma unroll
   for (int kk = 0; kk < D / 16; ++kk) {
     if (wave_active) {
-      const int64_t o = kv_off + (int64_t)(kvw0 + l32) * p.kv_st + 16 * kk + 8 * half;
+      const int64_t o = kv_off + (int64_t)(VARLEN ? min(kvw0 + l32, N - 1) : kvw0 + l32) * p.kv_st + 16 * kk + 8 * half;
       kf[kk] = *reinterpret_cast<const bf16x8*>(p.k + o);
       vf[kk] = *reinterpret_cast<const bf16x8*>(p.v + o);
     } else {
@@ -399,7 +461,7 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
   wait_all_loads();
   __syncthreads();
 
-  for (int it = 0; it < total; ++it) {
+  for (int it = it0; it < total; ++it) {
     const int buf = it & 1;
     int ln = lane;
     asm volatile("" : "+v"(ln));
@@ -423,6 +485,7 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
       for (int qt = 0; qt < QT; ++qt) {
         const int qbase = q0 + 32 * qt;
         if (qbase + 31 < kvw0) continue;  // every query of this half-chunk lies before my keys
+        if (VARLEN && qbase >= N) continue;  // ... or after the end of my sequence
         f32x16 s = f32x16{}, dp = f32x16{};
 #pragma unroll
         for (int kk = 0; kk < D / 16; ++kk) s = mfma32(Tile::row_frag(qs, qt, kk, l32, half), kf[kk], s);
@@ -433,6 +496,8 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
         // (the dense instantiation keeps the plain comparison: with this form the compiler spills there)
         const bool diag = qbase < kvw0 + 31;
         const int lim = diag ? key - qbase - 4 * half : -1;
+        // packed batch: query row 8g + 4 half + e of the half-chunk exists iff 8g + e < rows_left
+        const int rows_left = VARLEN ? N - qbase - 4 * half : 0;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const int r0 = 32 * qt + 8 * g + 4 * half;
@@ -444,8 +509,13 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
             float pr = fast_exp2(__builtin_fmaf(s[r], c, -l4[e]));
             if (DENSE ? (diag && key > q0 + r0 + e) : (lim > 8 * g + e)) pr = 0.f;
             if (CH == 32 && !((mine >> (g >> 1)) & 1)) pr = 0.f;  // query rows 0..15: block 0, 16..31: block 1
+            float ds = pr * (dp[r] - d4[e]);
+            if (VARLEN && 8 * g + e >= rows_left) {  // a row past the sequence's end: its statistics are not its own
+              pr = 0.f;
+              ds = 0.f;
+            }
             s[r] = pr;
-            dp[r] = pr * (dp[r] - d4[e]);
+            dp[r] = ds;
           }
         }
 #pragma unroll
@@ -467,7 +537,7 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
     __syncthreads();
   }
 
-  if (!wave_active) return;
+  if (!wave_active || (VARLEN && kvw0 + l32 >= N)) return;
   uint16_t* dk_row = p.dk + kv_off + (int64_t)(kvw0 + l32) * p.kv_st;
   uint16_t* dv_row = p.dv + kv_off + (int64_t)(kvw0 + l32) * p.kv_st;
 #pragma unroll
@@ -504,32 +574,35 @@ hipError_t set_smem(K kernel, size_t bytes, SmemSet& flags) {
   return e;
 }
 
-template <int D, bool DENSE, int CH>
+template <int D, bool DENSE, int CH, bool VARLEN = false>
 hipError_t launch_one(const AttnParams& p, int stages, hipStream_t stream) {
   static SmemSet dq_set, dkdv_set;  // zero-initialised
-  hipError_t e = set_smem(&dq_kernel<D, DENSE, CH>, sizeof(DqSmem<D, CH>), dq_set);
+  hipError_t e = set_smem(&dq_kernel<D, DENSE, CH, VARLEN>, sizeof(DqSmem<D, CH>), dq_set);
   if (e != hipSuccess) return e;
-  e = set_smem(&dkdv_kernel<D, DENSE, CH>, sizeof(DkvSmem<D, CH>), dkdv_set);
+  e = set_smem(&dkdv_kernel<D, DENSE, CH, VARLEN>, sizeof(DkvSmem<D, CH>), dkdv_set);
   if (e != hipSuccess) return e;
 
   const int64_t rows = (int64_t)p.batch * p.heads * p.seqlen;
   constexpr int RPB = 256 / (D / 8);
   // The dQ kernel computes delta itself and leaves it (and LSE in base-2 units) in the workspace,
-  // so it runs first and the stand-alone delta kernel only when dQ is not part of the call.
-  if ((stages & kBwdDelta) && !(stages & kBwdDq)) {
+  // so it runs first and the stand-alone delta kernel only when dQ is not part of the call
+  // (a packed batch is always a whole backward).
+  if (!VARLEN && (stages & kBwdDelta) && !(stages & kBwdDq)) {
     hipLaunchKernelGGL((delta_kernel<D>), dim3((unsigned)((rows + RPB - 1) / RPB)), dim3(256), 0, stream, p);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   const int bh = p.batch * p.heads;
   if (stages & kBwdDq) {
-    hipLaunchKernelGGL((dq_kernel<D, DENSE, CH>), dim3(grid_for(bh, p.q_tiles.tiles_per_head)), dim3(kThreads),
+    // one slot per 128-row tile: of the sequence, or of the longest length a packed batch allows
+    const int q_tiles = VARLEN ? (p.q_rows + kBwdBM - 1) / kBwdBM : p.q_tiles.tiles_per_head;
+    hipLaunchKernelGGL((dq_kernel<D, DENSE, CH, VARLEN>), dim3(grid_for(bh, q_tiles)), dim3(kThreads),
                        sizeof(DqSmem<D, CH>), stream, p);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   if (stages & kBwdDkDv) {
-    hipLaunchKernelGGL((dkdv_kernel<D, DENSE, CH>), dim3(grid_for(bh, p.kv_tiles.tiles_per_head)),
+    hipLaunchKernelGGL((dkdv_kernel<D, DENSE, CH, VARLEN>), dim3(grid_for(bh, p.kv_tiles.tiles_per_head)),
                        dim3(kThreads), sizeof(DkvSmem<D, CH>), stream, p);
     e = hipGetLastError();
   }
@@ -539,6 +612,13 @@ hipError_t launch_one(const AttnParams& p, int stages, hipStream_t stream) {
 }  // namespace
 
 hipError_t launch_bwd(const AttnParams& p, bool dense, int stages, hipStream_t stream) {
+  if (!dense && p.cu_seqlens) {  // packed variable-length batch: a whole backward, sparse layouts only
+    if (p.block_size <= 32)
+      return p.head_dim == 128 ? launch_one<128, false, 32, true>(p, kBwdAll, stream)
+                               : launch_one<64, false, 32, true>(p, kBwdAll, stream);
+    return p.head_dim == 128 ? launch_one<128, false, kChunk, true>(p, kBwdAll, stream)
+                             : launch_one<64, false, kChunk, true>(p, kBwdAll, stream);
+  }
   // 32-token mask blocks are walked in steps of 32 rows, everything else in steps of 64
   if (!dense && p.block_size <= 32)
     return p.head_dim == 128 ? launch_one<128, false, 32>(p, stages, stream) : launch_one<64, false, 32>(p, stages, stream);

@@ -1,0 +1,116 @@
+"""GPU parity of the backward on packed variable-length batches (s2_attn_bwd_varlen) against the
+fp64 oracle: ragged lengths, empty sequences, rows owned by no sequence, every block size, a custom
+pattern, and bit-identity with the fixed-length backward."""
+
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import s2_oracle as orc
+from paper_2407_17678_amd import binding as B
+from paper_2407_17678_amd import synth
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+LSE_TOL, GRAD_TOL = 1e-3, 2e-2
+SENTINEL = 0x4248  # bf16 50.0: what the outputs hold where the kernels must not write
+
+
+def _run(w, H, lens, Bk, M=None, extra_rows=0):
+    S, D = w.block_size, w.head_dim
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    total = int(cu[-1]) + extra_rows
+    qb, kb, vb, gb = synth.train_inputs(w, heads=H, batch=1, seqlen=total)
+    if M is None:
+        M = orc.block_mask(H, Bk, w.local_blocks, w.stride)
+        lay = B.s2_layout_build(B.layout_params(H, Bk, S, w.local_blocks, w.stride))
+    else:
+        row_ptr, col_idx, _, _ = orc.compressed_layout(M)
+        lay = B.s2_layout_from_csr(H, Bk, S, row_ptr, col_idx)
+    q, k, v, g = G.to_dev(qb), G.to_dev(kb), G.to_dev(vb), G.to_dev(gb)
+    sent = lambda: torch.full_like(q.view(torch.int16), SENTINEL).view(q.dtype)
+    o, dq, dk, dv = sent(), sent(), sent(), sent()
+    lse = torch.full((H, total), 77.0, dtype=torch.float32, device="cuda")
+    cud = torch.from_numpy(cu).cuda()
+    # the workspace starts out as NaN: the slack the kernels read past a sequence's end must not matter
+    ws = torch.full((B.s2_attn_bwd_varlen_workspace_bytes(H, total, D) // 4,), float("nan"), dtype=torch.float32,
+                    device="cuda")
+    B.s2_attn_fwd_varlen(lay, q, k, v, o, lse, cud, Bk * S, w.scale)
+    B.s2_attn_bwd_varlen(lay, q, k, v, o, lse, g, dq, dk, dv, cud, Bk * S, w.scale, ws)
+    torch.cuda.synchronize()
+    return (qb, kb, vb, gb), cu, M, dict(o=o, lse=lse, dq=dq, dk=dk, dv=dv)
+
+
+def _check(bits, cu, M, S, scale, out, end):
+    f = G.bits_f64
+    qb, kb, vb, gb = bits
+    dQ, dK, dV, O, LSE = orc.attention_backward_varlen(f(qb)[0], f(kb)[0], f(vb)[0], f(gb)[0], cu, M, S, scale)
+    assert G.o_excess(G.to_f64(out["o"])[0, :, :end], O[:, :end]) <= 0
+    assert np.abs(G.to_f64(out["lse"])[:, :end] - LSE[:, :end]).max() <= LSE_TOL
+    for n, ref in (("dq", dQ), ("dk", dK), ("dv", dV)):
+        got = G.to_f64(out[n])[0, :, :end]
+        assert np.isfinite(got).all(), n
+        # per sequence, so that a short sequence is not drowned by a long one
+        # (a one-token sequence has dQ = dK = 0 exactly: the relative bound gets an absolute floor of
+        # 1e-3 rms, far below the gradients' own scale of about 1)
+        for lo, hi in zip(cu[:-1], cu[1:]):
+            if hi > lo:
+                a, b = got[:, lo:hi], ref[:, lo:hi]
+                err = np.linalg.norm(a - b)
+                assert err <= GRAD_TOL * max(np.linalg.norm(b), 1e-3 * np.sqrt(b.size)), (n, int(lo), int(hi), err)
+        assert (out[n].view(torch.int16)[0, :, end:] == SENTINEL).all(), n
+
+
+CASES = {
+    # name: (workload for D / seed, S, heads, layout blocks, B_l, stride, lengths)
+    "S64_D128": ("1p3b_8k", 64, 3, 16, 2, 3, [1, 127, 128, 129, 700, 64, 0, 333, 1024]),
+    "S16_D64": ("tiny", 16, 4, 16, 2, 5, [5, 16, 17, 31, 100, 250, 256, 33]),
+    "S128_D128": ("7b_128k", 128, 2, 8, 2, 3, [130, 384, 1, 1000, 257]),
+    "S32_D128": ("1p3b_8k", 32, 3, 20, 3, 4, [31, 32, 33, 95, 640, 2, 161]),
+    "S64_D64_many_short": ("tiny", 64, 2, 4, 1, 2, [3, 9, 1, 64, 65, 12, 200, 7, 130, 256, 40, 99, 128, 5]),
+}
+
+
+@pytest.mark.parametrize("case", sorted(CASES))
+def test_varlen_backward_against_the_oracle(case):
+    wname, S, H, Bk, B_l, s, lens = CASES[case]
+    w = dataclasses.replace(synth.WORKLOADS[wname], block_size=S, local_blocks=B_l, stride=s)
+    print("varlen backward case", case, "H", H, "S", S, "B", Bk, "lens", lens, flush=True)
+    bits, cu, M, out = _run(w, H, lens, Bk, extra_rows=70)
+    _check(bits, cu, M, S, w.scale, out, int(cu[-1]))
+
+
+def test_varlen_backward_custom_pattern():
+    w = dataclasses.replace(synth.WORKLOADS["1p3b_8k"], block_size=32)
+    H, Bk, S = 2, 24, 32
+    rng = np.random.default_rng(17)
+    M = np.tril(rng.random((H, Bk, Bk)) < 0.3)
+    i = np.arange(Bk)
+    M[:, i, i] = True
+    bits, cu, M, out = _run(w, H, [700, 45, 768, 129], Bk, M=M)
+    _check(bits, cu, M, S, w.scale, out, int(cu[-1]))
+
+
+def test_varlen_backward_equals_the_fixed_length_backward_bit_for_bit():
+    # each sequence on its own through s2_attn_fwd / s2_attn_bwd (lengths they accept: whole blocks)
+    w = dataclasses.replace(synth.WORKLOADS["1p3b_8k"], block_size=64, local_blocks=2, stride=3)
+    H, Bk, S, D = 3, 12, 64, 128
+    lens = [768, 64, 320, 128]
+    bits, cu, M, out = _run(w, H, lens, Bk)
+    q, k, v, g = (G.to_dev(x) for x in bits)
+    for sq, L in enumerate(lens):
+        lo = int(cu[sq])
+        lay = B.s2_layout_build(B.layout_params(H, L // S, S, w.local_blocks, w.stride))
+        qs, ks, vs, gs = (x[:, :, lo:lo + L].contiguous() for x in (q, k, v, g))
+        o1 = torch.empty_like(qs)
+        lse1 = torch.empty((1, H, L), dtype=torch.float32, device="cuda")
+        d1 = [torch.empty_like(qs) for _ in range(3)]
+        ws = torch.empty(B.s2_attn_bwd_workspace_bytes(1, H, L, D), dtype=torch.uint8, device="cuda")
+        B.s2_attn_fwd(lay, qs, ks, vs, o1, lse1, w.scale)
+        B.s2_attn_bwd(lay, qs, ks, vs, o1, lse1, gs, d1[0], d1[1], d1[2], w.scale, ws)
+        torch.cuda.synchronize()
+        for n, t in zip(("dq", "dk", "dv"), d1):
+            assert torch.equal(t, out[n][:, :, lo:lo + L]), (sq, n)

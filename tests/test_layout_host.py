@@ -372,3 +372,23 @@ def test_block_count_limits_of_the_tile_lists():
     lib.s2_layout_destroy(out)
     too_many16 = B.layout_params(1, 65538, 16, 1, 0)
     assert lib.s2_layout_build(C.byref(too_many16), C.byref(out)) == -8
+
+
+def test_varlen_backward_argument_errors_without_launch():
+    lib = B.lib()
+    lay = B.s2_layout_build(B.layout_params(2, 8, 64, 2, 4))
+    t = _tensors(batch=1, heads=2, seqlen=700)
+    need = lib.s2_attn_bwd_varlen_workspace_bytes(2, 700, 128)
+    assert need >= 2 * (2 * 700 + 64) * 4 and need % 256 == 0
+    assert lib.s2_attn_bwd_varlen_workspace_bytes(0, 700, 128) == 0
+    call = lambda t, cu=4096, n=3, mx=512, ws=256, nbytes=need: lib.s2_attn_bwd_varlen(
+        lay.handle, C.byref(t), cu, n, mx, 1.0, ws, nbytes, None)
+    assert lib.s2_attn_bwd_varlen(None, C.byref(t), 4096, 3, 512, 1.0, 256, need, None) == -1
+    assert call(t, cu=None) == -1
+    assert call(_tensors(batch=1, heads=2, seqlen=700, dq=None)) == -1
+    assert call(_tensors(batch=2, heads=2, seqlen=700)) == -3
+    assert call(t, mx=8 * 64 + 1) == -3
+    assert call(t, ws=None) == -5 and call(t, nbytes=need - 1) == -5 and call(t, ws=264) == -5
+    import torch
+    if not torch.cuda.is_available():
+        assert call(t) == -7
