@@ -208,3 +208,20 @@ def test_7b_prefill_varlen_full():
             idx = torch.from_numpy(rows + lo).cuda()
             assert G.o_excess(G.to_f64(o[0, h][idx]), O) <= 0, (sq, h)
             assert np.abs(G.to_f64(lse[h][idx]) - LSE).max() <= 1e-3, (sq, h)
+    # the backward of the same packed batch: whole (sequence, head) pairs against the oracle
+    gb = synth.train_inputs(w, heads=H, batch=1, seqlen=total)[3]
+    g = G.to_dev(gb)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+    ws = torch.empty(B.s2_attn_bwd_varlen_workspace_bytes(H, total, D), dtype=torch.uint8, device="cuda")
+    B.s2_attn_bwd_varlen(lay, q, k, v, o, lse, g, dq, dk, dv, torch.from_numpy(cu).cuda(), w.seqlen, w.scale, ws)
+    torch.cuda.synchronize()
+    for t in (dq, dk, dv):
+        assert torch.isfinite(t.float()).all()
+    for sq, h in ((10, 3), (8, 30), (1, 17)):    # 8553, 1966 and 13231 tokens, ragged ends
+        lo, L = int(cu[sq]), int(lens[sq])
+        f = lambda x: G.bits_f64(x[0, h, lo:lo + L])
+        dQ, dK, dV, _, _ = orc.attention_backward_head(f(qb), f(kb), f(vb), f(gb), M[h], S, w.scale)
+        for n, got, ref in (("dq", dq, dQ), ("dk", dk, dK), ("dv", dv, dV)):
+            e = G.rel_l2(G.to_f64(got[0, h, lo:lo + L]), ref)
+            print("   varlen %s seq %d head %d rel-L2 %.3e" % (n, sq, h, e), flush=True)
+            assert e <= 2e-2, (n, sq, h, e)
