@@ -1,6 +1,6 @@
 // Forward kernel: block-sparse causal attention with per-head lists of kept KV blocks
 // (section 3.2: iterate K/V tiles through on-chip memory, softmax over the kept keys only;
-// section 4.2: which blocks a head keeps).  One workgroup owns a query tile of 128*QT rows that
+// section 4.2: which blocks a head keeps).  One workgroup owns a query tile of 128 rows that
 // spans several mask rows (the Merge-Q idea of section 3.2: a big tile, a fine mask); it walks
 // the merged list of KV blocks any of its rows keeps, and each wavefront skips the blocks its own
 // mask row does not keep.
