@@ -165,6 +165,28 @@ int s2_layout_from_csr(int32_t num_heads, int32_t num_blocks, int32_t block_size
 int s2_layout_destroy(s2_layout* layout);
 int s2_layout_get(const s2_layout* layout, s2_layout_view* out);
 
+/* The work lists the kernels walk, for inspection (section 3.2's Merge-Q: one 128-row query tile
+ * serves `group` fine mask rows; its mirror image for key tiles).  HOST pointers into the handle.
+ * For head h and tile t the list is ent[ptr[h*T + t] .. ptr[h*T + t + 1]), each entry
+ * (unit << 16) | bits: `unit` is a partner block, or with 16-token blocks a pair of adjacent
+ * partner blocks (blocks_per_unit = 2), and bit r*blocks_per_unit + c says that member r of the
+ * tile keeps block unit*blocks_per_unit + c.  Row tiles (which = S2_TILES_FWD, S2_TILES_DQ): member
+ * r is block row t*group + r, partners are KV block columns, ascending.  Column tiles
+ * (S2_TILES_DKDV): member r is block column members[(h*T + t)*group + r] (-1 = none), partners are
+ * query block rows, descending.  order[h*T + k] is the k-th tile of head h by descending length.
+ * Errors: NULL, BAD_PARAM (which). */
+enum { S2_TILES_FWD = 0, S2_TILES_DQ = 1, S2_TILES_DKDV = 2 };
+typedef struct {
+  const int32_t* ptr;      /* [H*T + 1]                              */
+  const int32_t* ent;      /* [ptr[H*T]]                             */
+  const int32_t* order;    /* [H*T]                                  */
+  const int32_t* members;  /* [H*T*group]                            */
+  int32_t tiles_per_head;  /* T                                      */
+  int32_t group;           /* members per tile                       */
+  int32_t blocks_per_unit; /* 1, or 2 with 16-token blocks           */
+} s2_tile_view;
+int s2_layout_get_tiles(const s2_layout* layout, int which, s2_tile_view* out);
+
 /* ---- forward (section 3.2: softmax over the kept keys only) ------------------------------ */
 
 /* O = softmax(scale * Q K^T restricted to the mask) V, LSE = natural-log sum-exp of the scaled

@@ -46,6 +46,12 @@ class LayoutView(C.Structure):
                 ("on_device", C.c_int32)]
 
 
+class TileView(C.Structure):
+    _fields_ = [("ptr", C.POINTER(C.c_int32)), ("ent", C.POINTER(C.c_int32)), ("order", C.POINTER(C.c_int32)),
+                ("members", C.POINTER(C.c_int32)), ("tiles_per_head", C.c_int32), ("group", C.c_int32),
+                ("blocks_per_unit", C.c_int32)]
+
+
 class Tensors(C.Structure):
     _fields_ = [("q", C.c_void_p), ("k", C.c_void_p), ("v", C.c_void_p), ("o", C.c_void_p),
                 ("lse", C.c_void_p), ("d_o", C.c_void_p), ("dq", C.c_void_p), ("dk", C.c_void_p),
@@ -73,7 +79,7 @@ class PagedDecodeArgs(C.Structure):
 
 
 EXPORTS = (
-    "s2_layout_build", "s2_layout_from_csr", "s2_layout_destroy", "s2_layout_get", "s2_attn_fwd", "s2_attn_fwd_rows", "s2_attn_fwd_varlen", "s2_attn_bwd_varlen",
+    "s2_layout_build", "s2_layout_from_csr", "s2_layout_destroy", "s2_layout_get", "s2_layout_get_tiles", "s2_attn_fwd", "s2_attn_fwd_rows", "s2_attn_fwd_varlen", "s2_attn_bwd_varlen",
     "s2_attn_bwd_varlen_workspace_bytes", "s2_attn_bwd",
     "s2_attn_bwd_workspace_bytes", "s2_attn_bwd_stages", "s2_dense_causal_fwd", "s2_dense_causal_bwd", "s2_attn_decode",
     "s2_attn_decode_workspace_bytes", "s2_attn_decode_default_splits", "s2_attn_decode_paged",
@@ -98,6 +104,7 @@ def lib():
                                      C.POINTER(C.c_int32), C.POINTER(C.c_void_p)]
     L.s2_layout_destroy.argtypes = [C.c_void_p]
     L.s2_layout_get.argtypes = [C.c_void_p, C.POINTER(LayoutView)]
+    L.s2_layout_get_tiles.argtypes = [C.c_void_p, C.c_int, C.POINTER(TileView)]
     L.s2_attn_fwd.argtypes = [C.c_void_p, C.POINTER(Tensors), C.c_float, C.c_void_p]
     L.s2_attn_fwd_rows.argtypes = [C.c_void_p, C.POINTER(Tensors), C.c_int32, C.c_int32, C.c_float, C.c_void_p]
     L.s2_attn_fwd_varlen.argtypes = [C.c_void_p, C.POINTER(Tensors), C.c_void_p, C.c_int32, C.c_int32, C.c_float,
@@ -209,6 +216,22 @@ def s2_layout_get(layout):
         "block_size": v.block_size, "max_row_blocks": v.max_row_blocks,
         "covers_all": v.covers_all, "on_device": v.on_device,
     }
+
+
+TILES_FWD, TILES_DQ, TILES_DKDV = 0, 1, 2
+
+
+def s2_layout_get_tiles(layout, which):
+    """Host copies of one of the layout's work lists (see s2_tile_view in the header)."""
+    v = TileView()
+    _check(lib().s2_layout_get_tiles(layout.handle, which, C.byref(v)), "s2_layout_get_tiles")
+    heads = s2_layout_get(layout)["num_heads"]
+    n = heads * v.tiles_per_head
+    as_np = lambda p, k: np.ctypeslib.as_array(p, shape=(k,)).copy() if k else np.zeros(0, np.int32)
+    ptr = as_np(v.ptr, n + 1)
+    return {"ptr": ptr, "ent": as_np(v.ent, int(ptr[-1])), "order": as_np(v.order, n),
+            "members": as_np(v.members, n * v.group), "tiles_per_head": v.tiles_per_head, "group": v.group,
+            "blocks_per_unit": v.blocks_per_unit}
 
 
 def bf16_bits_to_device(bits, device="cuda"):

@@ -230,6 +230,20 @@ int s2_layout_get(const s2_layout* L, s2_layout_view* out) {
   return S2_OK;
 }
 
+int s2_layout_get_tiles(const s2_layout* L, int which, s2_tile_view* out) {
+  if (!L || !out) return S2_ERR_NULL;
+  if (which != S2_TILES_FWD && which != S2_TILES_DQ && which != S2_TILES_DKDV) return S2_ERR_BAD_PARAM;
+  const s2::TileList& t = which == S2_TILES_FWD ? L->fwd_tiles : which == S2_TILES_DQ ? L->q_tiles : L->kv_tiles;
+  out->ptr = t.ptr.data();
+  out->ent = t.ent.data();
+  out->order = t.order.data();
+  out->members = t.members.data();
+  out->tiles_per_head = t.tiles_per_head;
+  out->group = t.group;
+  out->blocks_per_unit = L->p.block_size < 32 ? 32 / L->p.block_size : 1;
+  return S2_OK;
+}
+
 int s2_attn_fwd(const s2_layout* layout, const s2_tensors* t, float scale, void* stream) {
   if (!layout) return S2_ERR_NULL;
   int st = check_tensors(t, false, scale);

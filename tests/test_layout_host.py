@@ -392,3 +392,66 @@ def test_varlen_backward_argument_errors_without_launch():
     import torch
     if not torch.cuda.is_available():
         assert call(t) == -7
+
+
+def _mask_from_tiles(lay, which, H, Bk):
+    """Rebuilds the block mask from one of the kernels' work lists, checking its shape on the way."""
+    t = B.s2_layout_get_tiles(lay, which)
+    T, G, sub = t["tiles_per_head"], t["group"], t["blocks_per_unit"]
+    cols = which == B.TILES_DKDV
+    M = np.zeros((H, Bk, Bk), dtype=bool)
+    seen_members = [set() for _ in range(H)]
+    for h in range(H):
+        lens = []
+        for tile in range(T):
+            lo, hi = int(t["ptr"][h * T + tile]), int(t["ptr"][h * T + tile + 1])
+            lens.append(hi - lo)
+            mem = t["members"][(h * T + tile) * G:(h * T + tile + 1) * G] if len(t["members"]) else None
+            members = [int(m) for m in mem] if cols else [tile * G + r if tile * G + r < Bk else -1 for r in range(G)]
+            if cols:
+                seen_members[h].update(m for m in members if m >= 0)
+                if sub > 1:    # a wavefront's 32 key rows span two members: they must be adjacent columns
+                    real = [m for m in members if m >= 0]
+                    assert real == list(range(real[0], real[0] + len(real)))
+            units = [int(e) >> 16 for e in t["ent"][lo:hi]]
+            assert units == sorted(set(units), reverse=cols), "partners strictly ordered, none twice"
+            for e in t["ent"][lo:hi]:
+                unit, bits = int(e) >> 16, int(e) & 0xFFFF
+                assert bits != 0 and bits < (1 << (G * sub))
+                for r in range(G):
+                    for c in range(sub):
+                        if (bits >> (r * sub + c)) & 1:
+                            assert members[r] >= 0
+                            partner = unit * sub + c
+                            i, j = (partner, members[r]) if cols else (members[r], partner)
+                            assert not M[h, i, j], "a block listed twice"
+                            M[h, i, j] = True
+        order = [int(x) for x in t["order"][h * T:(h + 1) * T]]
+        assert sorted(order) == list(range(T))
+        assert [lens[x] for x in order] == sorted(lens, reverse=True), "longest tiles first"
+        if cols:
+            assert seen_members[h] == set(range(Bk)), "every column belongs to exactly one key tile"
+    return M
+
+
+@pytest.mark.parametrize("S", [16, 32, 64, 128])
+def test_work_lists_hold_exactly_the_mask(S):
+    # the lists the three kernels walk (merged query tiles, merged key tiles) against the oracle's
+    # mask, for the rule and for arbitrary patterns, every block size
+    rng = np.random.default_rng(40 + S)
+    cases = [orc.block_mask(5, 24, 3, 4), orc.block_mask(3, 10, 1, 0), orc.with_sink(orc.block_mask(2, 18, 2, 7), 1)]
+    cases += [_random_causal_mask(rng, int(rng.integers(1, 5)), 2 * int(rng.integers(1, 20)), float(rng.random()))
+              for _ in range(6)]
+    for M in cases:
+        H, Bk, _ = M.shape
+        row_ptr, col_idx, _, _ = orc.compressed_layout(M)
+        lay = B.s2_layout_from_csr(H, Bk, S, row_ptr, col_idx)
+        for which in (B.TILES_FWD, B.TILES_DQ, B.TILES_DKDV):
+            assert np.array_equal(_mask_from_tiles(lay, which, H, Bk), M), (S, which)
+    lay = B.s2_layout_build(B.layout_params(4, 32, S, 3, 5, 2))
+    want = orc.block_mask(4, 32, 3, 5, 2)
+    for which in (B.TILES_FWD, B.TILES_DQ, B.TILES_DKDV):
+        assert np.array_equal(_mask_from_tiles(lay, which, 4, 32), want)
+    v = B.TileView()
+    assert B.lib().s2_layout_get_tiles(lay.handle, 3, C.byref(v)) == -2
+    assert B.lib().s2_layout_get_tiles(None, 0, C.byref(v)) == -1
