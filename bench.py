@@ -95,6 +95,9 @@ def bench_train(w, steps, warmup, with_dense=True, with_bwd=True, dense_steps=3,
     lay = B.s2_layout_build(B.layout_params(H, N // S, S, w.local_blocks, w.stride, 0, w.window_blocks, 0))
     layout_ms = (time.time() - t0) * 1e3
     nnz = B.s2_layout_get(lay)["nnz"]
+    # KV-block loads of the forward: one per list entry of a merged 128-row query tile, against one
+    # per kept block of every S-token mask row without merging (the reload accounting of section 3.2)
+    merged = int(B.s2_layout_get_tiles(lay, B.TILES_FWD)["ptr"][-1])
     pairs = sparse_pairs(nnz, H, N // S, S) * Bt
     dense_pairs = H * N * (N + 1) // 2 * Bt
 
@@ -113,7 +116,7 @@ def bench_train(w, steps, warmup, with_dense=True, with_bwd=True, dense_steps=3,
 
     res = dict(workload=w.name, batch=Bt, heads=H, seqlen=N, head_dim=D, block_size=S,
                local_blocks=w.local_blocks, stride=w.stride, nnz_blocks=int(nnz),
-               layout_build_ms=round(layout_ms, 2))
+               layout_build_ms=round(layout_ms, 2), kv_block_loads_per_head_set=dict(unmerged=int(nnz), merged=merged))
     # each kernel on its own (same stream, same inputs)
     res["ms_fwd"] = time_events(fwd, steps, 1)
     flops_fwd = 4.0 * D * pairs
