@@ -102,15 +102,20 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
 // The global address is a wave-uniform base (scalar registers) plus a per-lane unsigned 32-bit
 // byte offset, so a lane spends one register per load and no 64-bit address arithmetic.
 // The s_nop is the wait state a scalar write of M0 needs before an instruction that reads it (the
-// compiler would add it for its own code; it does not look inside inline assembly).
+// compiler would add it for its own code; it does not look inside inline assembly).  M0 is named
+// as clobbered so that the compiler does not expect a value of its own to survive there (it warns
+// that M0 is a reserved register; the clobber is honoured all the same).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void dma16(const void* gbase, uint32_t byte_off, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(gbase), "s"(lds_base)
-               : "memory");
+               : "memory", "m0");
 }
 __device__ __forceinline__ void dma4(const void* gbase, uint32_t byte_off, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(byte_off), "s"(gbase), "s"(lds_base)
-               : "memory");
+               : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 template <int D, int ROWS = 64>
 struct DmaTile {
