@@ -115,15 +115,54 @@ __device__ __forceinline__ void dma4(const void* gbase, uint32_t byte_off, uint3
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(byte_off), "s"(gbase), "s"(lds_base)
                : "memory", "m0");
 }
+// The same with the LDS address given as a wave-uniform base plus a compile-time offset, so that a
+// kernel with many load targets keeps one scalar register per stage instead of one per target.
+// No "memory" clobber: the compiler may move its own LDS reads across the load; the kernels that use
+// this form read a stage only after the wait and barrier that publish it.
+template <int OFF>
+__device__ __forceinline__ void dma16_at(const void* gbase, uint32_t byte_off, uint32_t lds_base) {
+  asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(gbase), "s"(lds_base),
+               "n"(OFF)
+               : "m0", "scc");
+}
+// Up to four loads that share one M0 value.  The instruction's immediate offset is added to the
+// global address AND to the LDS address, so loads whose LDS targets are 1 KiB apart need only
+// one scalar write of M0 (and one wait state) between them; the caller takes the immediate back
+// out of the lane's global offset.  kCount loads, the i-th with immediate 1024 * i.
+template <int kCount>
+__device__ __forceinline__ void dma16_group(const void* gbase, uint32_t lds_base, uint32_t o0, uint32_t o1,
+                                            uint32_t o2, uint32_t o3) {
+  static_assert(kCount >= 1 && kCount <= 4, "immediates 0 .. 3072");
+  if constexpr (kCount == 4)
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %2, %0\n\tglobal_load_lds_dwordx4 %3, %0 offset:1024\n\t"
+                 "global_load_lds_dwordx4 %4, %0 offset:2048\n\tglobal_load_lds_dwordx4 %5, %0 offset:3072"
+                 ::"s"(gbase), "s"(lds_base), "v"(o0), "v"(o1), "v"(o2), "v"(o3)
+                 : "m0");
+  else if constexpr (kCount == 3)
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %2, %0\n\tglobal_load_lds_dwordx4 %3, %0 offset:1024\n\t"
+                 "global_load_lds_dwordx4 %4, %0 offset:2048"
+                 ::"s"(gbase), "s"(lds_base), "v"(o0), "v"(o1), "v"(o2)
+                 : "m0");
+  else if constexpr (kCount == 2)
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %2, %0\n\tglobal_load_lds_dwordx4 %3, %0 offset:1024"
+                 ::"s"(gbase), "s"(lds_base), "v"(o0), "v"(o1)
+                 : "m0");
+  else
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %0" ::"s"(gbase), "s"(lds_base), "v"(o0)
+                 : "m0");
+}
 #pragma clang diagnostic pop
 
-template <int D, int ROWS = 64>
+template <int D, int ROWS = 64, int NW = 4>
 struct DmaTile {
   static constexpr int kStride = (D == 128) ? 152 : 104;  // elements
   static constexpr int kInstr = (ROWS * kStride * 2 + 1023) / 1024;  // wavefront-wide loads per tile
   static constexpr int kBytes = kInstr * 1024;            // the last load may run past the last row
   static constexpr int kElems = kBytes / 2;
-  static constexpr int kPerWave = (kInstr + 3) / 4;
+  static constexpr int kPerWave = (kInstr + NW - 1) / NW;  // NW wavefronts share the loads
 
   struct Plan {
     uint32_t goff[kPerWave];  // byte offset from the chunk's first row, per load of this lane
@@ -138,7 +177,7 @@ struct DmaTile {
     Plan pl;
 #pragma unroll
     for (int n = 0; n < kPerWave; ++n) {
-      const int instr = min(4 * n + wave, kInstr - 1);
+      const int instr = min(NW * n + wave, kInstr - 1);
       const int pos = instr * 1024 + lane * 16;
       int row = pos / (kStride * 2);
       int piece = (pos - row * kStride * 2) / 16;
@@ -156,7 +195,7 @@ struct DmaTile {
     const int last = max(rows_valid, 1) - 1;
 #pragma unroll
     for (int n = 0; n < kPerWave; ++n) {
-      const int instr = min(4 * n + wave, kInstr - 1);
+      const int instr = min(NW * n + wave, kInstr - 1);
       const int pos = instr * 1024 + lane * 16;
       int row = pos / (kStride * 2);
       int piece = (pos - row * kStride * 2) / 16;
@@ -171,8 +210,59 @@ struct DmaTile {
   // Complete after s_waitcnt vmcnt(0).
   __device__ static __forceinline__ void issue_one(const Plan& pl, int n, const uint16_t* gbase,
                                                    const uint16_t* tile, int wave) {
-    const int instr = min(4 * n + wave, kInstr - 1);
+    const int instr = min(NW * n + wave, kInstr - 1);
     dma16(gbase, pl.goff[n], lds_addr(tile) + instr * 1024);
+  }
+  // The same with n known at compile time: the LDS offset is an immediate.
+  template <int N_>
+  __device__ static __forceinline__ void issue_at(const Plan& pl, const uint16_t* gbase, const uint16_t* tile, int wave) {
+    static_assert(NW == 2, "the wavefront's share of the offset is folded into the base for two wavefronts");
+    // load N_ of wavefront `wave` is load NW * N_ + wave of the tile (the last one repeated if past the end)
+    constexpr int kLast = kInstr - 1;
+    if (NW * N_ + 1 <= kLast)
+      dma16_at<NW * N_ * 1024>(gbase, pl.goff[N_], lds_addr(tile) + wave * 1024);
+    else  // only wavefront 0's load exists; wavefront 1 repeats it (same data, same place)
+      dma16_at<kLast * 1024>(gbase, pl.goff[N_], lds_addr(tile));
+  }
+  // ---- loads dealt to the wavefronts in blocks, issued in groups of up to four per M0 write ----
+  // Wavefront w fetches kBlock consecutive loads of the tile (consecutive kilobytes of LDS),
+  // starting at load min(w * kBlock, kInstr - kBlock): where the blocks do not divide the tile
+  // evenly the last wavefront starts early and fetches a load or two twice (same data, same place)
+  // rather than having a shorter block, so that every wavefront runs the same instructions.  A group
+  // of four shares one M0 value and tells its loads apart by the instruction's immediate offset,
+  // which the hardware adds to the global address as well: the lane offsets of the plan have it
+  // taken out again, plus kBias so that they stay non-negative (the caller passes the chunk's
+  // address minus kBias bytes).
+  static constexpr int kBlock = (kInstr + NW - 1) / NW;
+  static constexpr int kGroups = (kBlock + 3) / 4;
+  static constexpr uint32_t kBias = 3072;
+  struct BlockPlan {
+    uint32_t goff[kBlock];
+  };
+  __device__ static __forceinline__ int block_start(int wave) { return min(wave * kBlock, kInstr - kBlock); }
+  __device__ static __forceinline__ BlockPlan block_plan(int64_t row_stride, int wave, int lane) {
+    BlockPlan pl;
+#pragma unroll
+    for (int n = 0; n < kBlock; ++n) {
+      const int pos = (block_start(wave) + n) * 1024 + lane * 16;
+      int row = pos / (kStride * 2);
+      int piece = (pos - row * kStride * 2) / 16;
+      if (piece >= D / 8) piece -= D / 8;
+      if (row >= ROWS) row = ROWS - 1;  // past the tile: lands in the slack after the last row
+      pl.goff[n] = (uint32_t)(row * row_stride * 2) + 16 * piece + kBias - 1024 * (n & 3);
+    }
+    return pl;
+  }
+  // group G of this wavefront's loads; gbase_biased = address of the chunk's first row minus kBias bytes
+  template <int G>
+  __device__ static __forceinline__ void issue_group(const BlockPlan& pl, const void* gbase_biased, const uint16_t* tile,
+                                                     int wave) {
+    static_assert(G >= 0 && G < kGroups, "group index");
+    constexpr int first = 4 * G;
+    constexpr int count = (kBlock - first) < 4 ? (kBlock - first) : 4;
+    const uint32_t lds = lds_addr(tile) + (block_start(wave) + first) * 1024;
+    dma16_group<count>(gbase_biased, lds, pl.goff[first], pl.goff[first + (count > 1 ? 1 : 0)],
+                       pl.goff[first + (count > 2 ? 2 : 0)], pl.goff[first + (count > 3 ? 3 : 0)]);
   }
   // All loads of one chunk.
   __device__ static __forceinline__ void issue(const Plan& pl, const uint16_t* gbase, const uint16_t* tile,
