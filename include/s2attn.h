@@ -273,6 +273,20 @@ size_t s2_attn_decode_workspace_bytes(int32_t nseq, int32_t heads, int32_t head_
  * splits when the pattern keeps so few blocks per row that more splits would leave wavefronts idle. */
 int32_t s2_attn_decode_default_splits(int32_t nseq, int32_t heads, int32_t max_len);
 
+/* For callers that cannot allocate or hold device memory for the library: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  s2_attn_decode with the split
+ * partials kept in a buffer of S2_DECODE_STATIC_SCRATCH_BYTES that is part of the loaded library
+ * (each GPU the library runs on holds its own copy until the process ends) instead of a caller's
+ * workspace; the call allocates and frees nothing and gives the same o and lse as s2_attn_decode.
+ * Shapes whose partials (s2_attn_decode_workspace_bytes of the same arguments) exceed that size
+ * are refused with S2_ERR_WORKSPACE before anything is launched: lower num_splits or use
+ * s2_attn_decode.  Every call on a GPU uses that GPU's one buffer, whatever the stream, and the
+ * buffer keeps the last call's partials (each call overwrites what it reads, so nothing needs
+ * clearing): calls that overlap in time on one GPU race; calls on one stream, or otherwise
+ * ordered, do not.  Errors: as s2_attn_decode, plus NO_DEVICE when no GPU is visible. */
+#define S2_DECODE_STATIC_SCRATCH_BYTES (8u << 20)
+int s2_attn_decode_static(const s2_layout_params* p, const s2_decode_args* a, float scale, void* stream);
+
 /* Same step against a paged cache.  A kept block whose table entry is negative (or not below
  * num_pages) contributes nothing and is counted in *missing when that pointer is given; blocks
  * the mask drops are never looked up, so their entries may hold anything.  A (sequence, head)

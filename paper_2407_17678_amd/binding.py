@@ -82,7 +82,7 @@ EXPORTS = (
     "s2_layout_build", "s2_layout_from_csr", "s2_layout_destroy", "s2_layout_get", "s2_layout_get_tiles", "s2_attn_fwd", "s2_attn_fwd_rows", "s2_attn_fwd_varlen", "s2_attn_bwd_varlen",
     "s2_attn_bwd_varlen_workspace_bytes", "s2_attn_bwd",
     "s2_attn_bwd_workspace_bytes", "s2_attn_bwd_stages", "s2_dense_causal_fwd", "s2_dense_causal_bwd", "s2_attn_decode",
-    "s2_attn_decode_workspace_bytes", "s2_attn_decode_default_splits", "s2_attn_decode_paged",
+    "s2_attn_decode_workspace_bytes", "s2_attn_decode_default_splits", "s2_attn_decode_static", "s2_attn_decode_paged",
     "s2_kv_resident_blocks", "s2_attn_decode_layout", "s2_attn_decode_paged_layout",
     "s2_layout_resident_blocks", "s2_status_string",
     "s2_last_hip_error", "s2_version",
@@ -122,6 +122,7 @@ def lib():
     L.s2_dense_causal_bwd.argtypes = [C.POINTER(Tensors), C.c_float, C.c_void_p, C.c_size_t, C.c_void_p]
     L.s2_attn_decode.argtypes = [C.POINTER(LayoutParams), C.POINTER(DecodeArgs), C.c_float, C.c_void_p,
                                  C.c_size_t, C.c_void_p]
+    L.s2_attn_decode_static.argtypes = [C.POINTER(LayoutParams), C.POINTER(DecodeArgs), C.c_float, C.c_void_p]
     L.s2_attn_decode_workspace_bytes.argtypes = [C.c_int32] * 5
     L.s2_attn_decode_workspace_bytes.restype = C.c_size_t
     L.s2_attn_decode_default_splits.argtypes = [C.c_int32] * 3
@@ -342,6 +343,19 @@ def s2_attn_decode(params, q, k_cache, v_cache, seq_lens, o, lse, scale, workspa
     _check(lib().s2_attn_decode(C.byref(params), C.byref(a), scale, _ptr(workspace),
                                 workspace.numel() * workspace.element_size(), _stream_ptr(stream)),
            "s2_attn_decode")
+
+
+def s2_attn_decode_static(params, q, k_cache, v_cache, seq_lens, o, lse, scale, max_len, num_splits=0,
+                          stream=None):
+    """s2_attn_decode with the split partials in the library's own static device buffer."""
+    nseq, H, D = q.shape
+    assert q.is_contiguous() and o.is_contiguous() and k_cache.stride() == v_cache.stride()
+    assert k_cache.stride(3) == 1
+    a = DecodeArgs(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seq_lens), _ptr(o), _ptr(lse),
+                   nseq, H, D, max_len, num_splits,
+                   k_cache.stride(0), k_cache.stride(1), k_cache.stride(2))
+    _check(lib().s2_attn_decode_static(C.byref(params), C.byref(a), scale, _stream_ptr(stream)),
+           "s2_attn_decode_static")
 
 
 def s2_attn_decode_layout(layout, q, k_cache, v_cache, seq_lens, o, lse, scale, workspace, max_len,

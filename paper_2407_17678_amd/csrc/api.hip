@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <limits>
@@ -65,6 +66,32 @@ s2::DevTiles dev_tiles(const s2::TileList& t) {
 }
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// The split partials of s2_attn_decode_static live here instead of in a caller's workspace: device
+// memory that belongs to the loaded library, one copy per GPU at that GPU's own address, held
+// until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the address found there, kept per device, is what the kernels are given.
+constexpr size_t kStaticScratchBytes = S2_DECODE_STATIC_SCRATCH_BYTES;
+__device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kScratchMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kScratchMaxDevices];  // zero-initialised: not looked up yet
+
+// Address of `scratch` on the current device, or nullptr (the hipError_t is kept for
+// s2_last_hip_error).  The first call on a device asks the runtime; later calls read the slot.
+void* scratch_on_current_device() {
+  int dev = -1;
+  if (!hip_ok(hipGetDevice(&dev))) return nullptr;
+  if (dev < 0 || dev >= kScratchMaxDevices) {
+    g_last_hip_error = (int)hipErrorInvalidDevice;
+    return nullptr;
+  }
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (ptr) return ptr;
+  if (!hip_ok(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch))) || !ptr) return nullptr;
+  g_scratch_ptr[dev].store(ptr, std::memory_order_release);  // racing threads store the same address
+  return ptr;
+}
 
 // Shape / alignment checks shared by forward and backward.  `need_bwd` also checks the
 // gradient tensors.
@@ -587,6 +614,25 @@ int s2_attn_decode(const s2_layout_params* lp, const s2_decode_args* a, float sc
                    size_t workspace_bytes, void* stream) {
   if (!lp || !a) return S2_ERR_NULL;
   return decode_contiguous(lp, nullptr, a, scale, workspace, workspace_bytes, stream);
+}
+
+int s2_attn_decode_static(const s2_layout_params* lp, const s2_decode_args* a, float scale, void* stream) {
+  if (!lp || !a) return S2_ERR_NULL;
+  // the size check comes first and needs no device: shapes whose partials do not fit are refused
+  if (a->nseq < 1 || a->heads < 1 || a->max_len < 1) return S2_ERR_SHAPE;
+  if (a->head_dim != 64 && a->head_dim != 128) return S2_ERR_SHAPE;
+  if (a->num_splits < 0 || a->num_splits > 64) return S2_ERR_BAD_PARAM;
+  // num_splits == 0: the call may pick fewer splits than this bound, never more
+  const size_t need = s2_attn_decode_workspace_bytes(a->nseq, a->heads, a->head_dim, a->max_len, a->num_splits);
+  if (need > kStaticScratchBytes) return S2_ERR_WORKSPACE;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) {
+    (void)hipGetLastError();
+    return S2_ERR_NO_DEVICE;
+  }
+  void* ptr = scratch_on_current_device();
+  if (!ptr) return S2_ERR_HIP;
+  return decode_contiguous(lp, nullptr, a, scale, ptr, kStaticScratchBytes, stream);
 }
 
 int s2_attn_decode_paged(const s2_layout_params* lp, const s2_paged_decode_args* a, float scale,
