@@ -62,17 +62,52 @@ def time_events(fn, steps, warmup):
 
 def measured_traffic(workload, kernel):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary
-    (profiles/traffic_<workload>.txt, lines `<kernel> <bytes>`), or None."""
+    (profiles/traffic_<workload>.txt, lines `<kernel> <bytes>`), or None.  The file names the
+    kernel sources it was measured on (`# sources <fingerprint>`, written by
+    paper_2407_17678_amd/profile_summary.py); a file taken on other sources is refused, so that the
+    figure cannot outlive the kernels it describes."""
+    from paper_2407_17678_amd import profile_summary
     path = os.path.join(ROOT, "profiles", "traffic_%s.txt" % workload)
     try:
         with open(path) as f:
-            for line in f:
-                parts = line.split()
-                if len(parts) >= 2 and parts[0] == kernel:
-                    return float(parts[1])
+            lines = f.read().splitlines()
     except OSError:
-        pass
+        return None
+    stamp = [l.split()[2] for l in lines if l.startswith("# sources ") and len(l.split()) >= 3]
+    if not stamp or stamp[0] != profile_summary.source_fingerprint():
+        log("[bench] %s was measured on other kernel sources: traffic not reported" % os.path.basename(path))
+        return None
+    for line in lines:
+        parts = line.split()
+        if len(parts) >= 2 and parts[0] == kernel:
+            return float(parts[1])
     return None
+
+
+def measured_ceilings():
+    """What the chip sustains on a pure MFMA loop (alone, and with a softmax's vector work per MFMA)
+    and on a pure read, timed like the kernels: the library's probe kernels (s2_probe_*), a few
+    milliseconds per launch on random operands."""
+    import torch
+    from paper_2407_17678_amd import binding as B
+    scratch = torch.empty(max(B.s2_probe_scratch_bytes(), 4 << 20), dtype=torch.uint8, device="cuda")
+    out = {}
+    for name, mix in (("mfma_bf16_tflops", 0), ("mfma_bf16_with_softmax_vector_work_tflops", 1)):
+        flops = [0.0]
+
+        def run():
+            flops[0] = B.s2_probe_mfma(mix, 20000, scratch)
+        prewarm(run, 0.2)
+        ms = time_events(run, 5, 1)
+        out[name] = flops[0] / (ms * 1e-3) / 1e12
+    src = torch.empty(2 << 30, dtype=torch.uint8, device="cuda").random_(0, 255)
+    rd = lambda: B.s2_probe_read(src, scratch)
+    prewarm(rd, 0.2)
+    ms = time_events(rd, 10, 2)
+    out["hbm_read_gbs"] = (2 << 30) / (ms * 1e-3) / 1e9
+    del src
+    torch.cuda.empty_cache()
+    return out
 
 
 def bench_train(w, steps, warmup, with_dense=True, with_bwd=True, dense_steps=3, hybrid_layers=None):
@@ -192,16 +227,26 @@ def bench_train(w, steps, warmup, with_dense=True, with_bwd=True, dense_steps=3,
 
     # roofline of the dominant kernel.  Flops attributed per kernel (sums to 14*D*pairs):
     # forward 4*D*pairs (QK^T, PV); dK/dV kernel 8*D*pairs (S, dP, dV, dK); dQ kernel 2*D*pairs.
-    kernels = {"fwd_kernel": (res["ms_fwd"], 4.0)}
+    # (head_dim 128 with mask blocks of 64 tokens or more runs the hand-scheduled forward and dQ kernels)
+    fast = D == 128 and S >= 64 and N % 128 == 0
+    kernels = {"fwd_pipe_kernel" if fast else "fwd_kernel": (res["ms_fwd"], 4.0)}
     if with_bwd:
         kernels["dkdv_kernel"] = (res["ms_bwd_dkdv"], 8.0)
-        kernels["dq_kernel"] = (res["ms_bwd_dq"], 2.0)
+        kernels["dq_pipe_kernel" if fast else "dq_kernel"] = (res["ms_bwd_dq"], 2.0)
     dom = max(kernels, key=lambda n: kernels[n][0])
     ach = kernels[dom][1] * D * pairs / (kernels[dom][0] * 1e-3) / 1e12
     res["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
                        "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": measured_traffic(w.name, dom),
                        "avg_launch_ms": kernels[dom][0],
                        "algorithmic_flops_per_launch": kernels[dom][1] * D * pairs}
+    if with_bwd:
+        # The attribution above is a convention (the dQ launch recomputes S and dP, which it is not
+        # credited with); the whole backward against its 10 * D * pairs says what the two launches deliver.
+        t_bwd = res["ms_bwd_dq"] + res["ms_bwd_dkdv"]
+        res["roofline"]["whole_backward"] = {"ms": t_bwd, "achieved": 10.0 * D * pairs / (t_bwd * 1e-3) / 1e12,
+                                             "frac": 10.0 * D * pairs / (t_bwd * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+        res["roofline"]["forward"] = {"ms": res["ms_fwd"], "achieved": res["tflops_fwd"],
+                                      "frac": res["tflops_fwd"] / PEAK_BF16_TFLOPS}
     tensors = dict(q=q, k=k, v=v, g=g, o=o, lse=lse, dq=dq, dk=dk, dv=dv, bits=(qb, kb, vb, gb))
     return res, tensors
 
@@ -419,7 +464,9 @@ def main():
     ap.add_argument("--cpu-sample-tokens", type=int, default=32768)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
-    ap.add_argument("--extra", action="store_true", help="also time the other workloads (reported under 'extra')")
+    ap.add_argument("--extra", action="store_true", help="(default) also time the other workloads, reported under 'extra'")
+    ap.add_argument("--no-extra", action="store_true", help="only the workload named by --workload")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the MFMA / HBM ceiling probes")
     ap.add_argument("--hybrid-stack", default=None, metavar="LAYERS:DENSE",
                     help="also time the attention of a LAYERS-layer stack with DENSE of them dense, e.g. 32:5")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -477,7 +524,11 @@ def main():
         return
 
     with_bwd = w.name != "7b_128k"
+    extras_on = not args.no_extra
+    if args.hybrid_stack is None and extras_on and w.name == "7b_32k":
+        args.hybrid_stack = "32:5"   # section 4.2: about 1/6 of a 7B model's 32 layers stay dense
     hybrid = tuple(int(x) for x in args.hybrid_stack.split(":")) if args.hybrid_stack else None
+
     res, tensors = bench_train(w, args.steps, args.warmup, with_dense=not args.no_dense, with_bwd=with_bwd,
                                dense_steps=2 if w.seqlen > 40000 else 3, hybrid_layers=hybrid)
     roof = res.pop("roofline")
@@ -490,15 +541,16 @@ def main():
     torch.cuda.empty_cache()
 
     extra = None
-    if args.extra:
+    if extras_on:
         extra = {}
-        for name in ("1p3b_8k", "7b_32k", "7b_128k"):
+        for name in ("tiny", "1p3b_8k", "7b_32k", "7b_128k"):
             if name == w.name:
                 continue
             ww = synth.WORKLOADS[name]
             r, t = bench_train(ww, max(3, args.steps // 2), 2, with_dense=not args.no_dense,
                                with_bwd=name != "7b_128k", dense_steps=1 if name == "7b_128k" else 3)
-            r.pop("roofline")
+            rf = r.pop("roofline")
+            r["roofline_frac_dominant_kernel"] = {"kernel": rf["kernel"], "frac": rf["frac"]}
             extra[name] = r
             del t
             torch.cuda.empty_cache()
@@ -506,6 +558,14 @@ def main():
         extra["7b_decode_paged"] = bench_decode_paged(synth.WORKLOADS["7b_decode"], 20, 3)
         extra["7b_prefill_varlen"] = bench_prefill_varlen(synth.WORKLOADS["7b_32k"], 10, 2)
 
+    # last, so that a second of pure MFMA load does not heat the chip under the numbers above
+    ceilings = None if args.no_ceilings else measured_ceilings()
+    if ceilings:
+        log("[bench] measured ceilings: %s" % ceilings)
+        roof["measured_peak"] = dict(ceilings, note="the library's probe kernels timed in this run: a pure MFMA loop on "
+                                     "random operands with two wavefronts per SIMD, alone and with a softmax's vector "
+                                     "work per MFMA beside it; a pure 2 GiB read")
+        roof["frac_of_measured_mfma"] = roof["achieved"] / ceilings["mfma_bf16_tflops"]
     out = {
         "metric": "effective sparse-attn TFLOP/s fwd+bwd (% MFMA peak) + speedup vs dense causal"
                   if with_bwd else "effective sparse-attn TFLOP/s fwd (% MFMA peak) + speedup vs dense causal",
@@ -522,6 +582,8 @@ def main():
         "cpu_baseline": cpu,
         "parity_on_cpu_sample": parity,
     }
+    if "hybrid_stack" in res:
+        out["hybrid_stack"] = res["hybrid_stack"]
     if extra is not None:
         out["extra"] = extra
     print(json.dumps(out))

@@ -322,6 +322,20 @@ int s2_attn_decode_paged_layout(const s2_layout* layout, const s2_paged_decode_a
 int s2_layout_resident_blocks(const s2_layout* layout, int32_t head, int32_t length,
                               int32_t* blocks, int32_t capacity, int32_t* count);
 
+/* ---- ceiling probes (measurement only) ------------------------------------------------------ */
+
+/* What the chip sustains on the two resources these kernels are bound by, for the benchmark to
+ * report beside the published peaks (the roofline section 5.3's comparison implies).  Each call
+ * only enqueues one kernel on `stream`; the caller times it.  scratch: DEVICE memory, at least
+ * s2_probe_scratch_bytes() for s2_probe_mfma and 4 MiB for s2_probe_read, overwritten.
+ * s2_probe_mfma: two wavefronts per SIMD issue 32x32x16 bf16 MFMAs back to back on random operands,
+ * `iters` trips of 8 each, optionally with a softmax's vector work per MFMA beside them; *flops
+ * receives the flops of the launch.  s2_probe_read: reads `bytes` (16-byte aligned) once.
+ * Errors: NULL, BAD_PARAM (iters), ALIGN, HIP. */
+size_t s2_probe_scratch_bytes(void);
+int s2_probe_mfma(int32_t with_vector_work, int32_t iters, void* scratch, void* stream, double* flops);
+int s2_probe_read(const void* src, size_t bytes, void* scratch, void* stream);
+
 /* ---- diagnostics -------------------------------------------------------------------------- */
 
 const char* s2_status_string(int status);

@@ -84,7 +84,7 @@ EXPORTS = (
     "s2_attn_bwd_workspace_bytes", "s2_attn_bwd_stages", "s2_dense_causal_fwd", "s2_dense_causal_bwd", "s2_attn_decode",
     "s2_attn_decode_workspace_bytes", "s2_attn_decode_default_splits", "s2_attn_decode_static", "s2_attn_decode_paged",
     "s2_kv_resident_blocks", "s2_attn_decode_layout", "s2_attn_decode_paged_layout",
-    "s2_layout_resident_blocks", "s2_status_string",
+    "s2_layout_resident_blocks", "s2_probe_scratch_bytes", "s2_probe_mfma", "s2_probe_read", "s2_status_string",
     "s2_last_hip_error", "s2_version",
 )
 
@@ -137,6 +137,9 @@ def lib():
                                               C.c_void_p, C.c_size_t, C.c_void_p]
     L.s2_layout_resident_blocks.argtypes = [C.c_void_p, C.c_int32, C.c_int32,
                                             C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_int32)]
+    L.s2_probe_scratch_bytes.restype = C.c_size_t
+    L.s2_probe_mfma.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(C.c_double)]
+    L.s2_probe_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
     L.s2_status_string.argtypes = [C.c_int]
     L.s2_status_string.restype = C.c_char_p
     L.s2_last_hip_error.restype = C.c_int
@@ -424,3 +427,22 @@ def s2_layout_resident_blocks(layout, head, length):
     _check(lib().s2_layout_resident_blocks(layout.handle, head, length, buf, n.value, C.byref(n)),
            "s2_layout_resident_blocks")
     return list(buf[:n.value])
+
+
+def s2_probe_scratch_bytes():
+    return int(lib().s2_probe_scratch_bytes())
+
+
+def s2_probe_mfma(with_vector_work, iters, scratch, stream=None):
+    """Enqueues the MFMA ceiling probe; returns the flops of the launch."""
+    flops = C.c_double(0.0)
+    _check(lib().s2_probe_mfma(int(bool(with_vector_work)), iters, _ptr(scratch), _stream_ptr(stream),
+                               C.byref(flops)), "s2_probe_mfma")
+    return flops.value
+
+
+def s2_probe_read(src, scratch, stream=None):
+    """Enqueues the read-bandwidth probe over the whole of `src`; returns the bytes read."""
+    nbytes = src.numel() * src.element_size()
+    _check(lib().s2_probe_read(_ptr(src), nbytes, _ptr(scratch), _stream_ptr(stream)), "s2_probe_read")
+    return nbytes

@@ -593,7 +593,10 @@ hipError_t launch_one(const AttnParams& p, int stages, hipStream_t stream) {
     if (e != hipSuccess) return e;
   }
   const int bh = p.batch * p.heads;
-  if (stages & kBwdDq) {
+  if ((stages & kBwdDq) && !VARLEN && CH == 64 && dq_pipe_applies(p, DENSE)) {
+    e = launch_dq_pipe(p, DENSE, stream);
+    if (e != hipSuccess) return e;
+  } else if (stages & kBwdDq) {
     // one slot per 128-row tile: of the sequence, or of the longest length a packed batch allows
     const int q_tiles = VARLEN ? (p.q_rows + kBwdBM - 1) / kBwdBM : p.q_tiles.tiles_per_head;
     hipLaunchKernelGGL((dq_kernel<D, DENSE, CH, VARLEN>), dim3(grid_for(bh, q_tiles)), dim3(kThreads),

@@ -115,16 +115,6 @@ __device__ __forceinline__ void dma4(const void* gbase, uint32_t byte_off, uint3
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(byte_off), "s"(gbase), "s"(lds_base)
                : "memory", "m0");
 }
-// The same with the LDS address given as a wave-uniform base plus a compile-time offset, so that a
-// kernel with many load targets keeps one scalar register per stage instead of one per target.
-// No "memory" clobber: the compiler may move its own LDS reads across the load; the kernels that use
-// this form read a stage only after the wait and barrier that publish it.
-template <int OFF>
-__device__ __forceinline__ void dma16_at(const void* gbase, uint32_t byte_off, uint32_t lds_base) {
-  asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(gbase), "s"(lds_base),
-               "n"(OFF)
-               : "m0", "scc");
-}
 // Up to four loads that share one M0 value.  The instruction's immediate offset is added to the
 // global address AND to the LDS address, so loads whose LDS targets are 1 KiB apart need only
 // one scalar write of M0 (and one wait state) between them; the caller takes the immediate back
@@ -212,17 +202,6 @@ struct DmaTile {
                                                    const uint16_t* tile, int wave) {
     const int instr = min(NW * n + wave, kInstr - 1);
     dma16(gbase, pl.goff[n], lds_addr(tile) + instr * 1024);
-  }
-  // The same with n known at compile time: the LDS offset is an immediate.
-  template <int N_>
-  __device__ static __forceinline__ void issue_at(const Plan& pl, const uint16_t* gbase, const uint16_t* tile, int wave) {
-    static_assert(NW == 2, "the wavefront's share of the offset is folded into the base for two wavefronts");
-    // load N_ of wavefront `wave` is load NW * N_ + wave of the tile (the last one repeated if past the end)
-    constexpr int kLast = kInstr - 1;
-    if (NW * N_ + 1 <= kLast)
-      dma16_at<NW * N_ * 1024>(gbase, pl.goff[N_], lds_addr(tile) + wave * 1024);
-    else  // only wavefront 0's load exists; wavefront 1 repeats it (same data, same place)
-      dma16_at<kLast * 1024>(gbase, pl.goff[N_], lds_addr(tile));
   }
   // ---- loads dealt to the wavefronts in blocks, issued in groups of up to four per M0 write ----
   // Wavefront w fetches kBlock consecutive loads of the tile (consecutive kilobytes of LDS),

@@ -14,8 +14,6 @@
 // read as row fragments, V through the LDS transpose read (DmaTile in device_util.h).
 #include <hip/hip_runtime.h>
 
-#include <cstdlib>
-
 #include "config.h"
 #include "device_util.h"
 #include "kernels.h"
@@ -311,10 +309,7 @@ hipError_t launch_one(const AttnParams& p, hipStream_t stream) {
 }  // namespace
 
 hipError_t launch_fwd(const AttnParams& p, bool dense, hipStream_t stream) {
-  static const bool use_old = getenv("S2_FWD_OLD") != nullptr;
-  static const bool use_64 = getenv("S2_FWD_64") != nullptr;
-  if (use_64 && fwd64_applies(p, dense)) return launch_fwd64(p, dense, stream);
-  if (!use_old && fwd_pipe_applies(p, dense)) return launch_fwd_pipe(p, dense, stream);
+  if (fwd_pipe_applies(p, dense)) return launch_fwd_pipe(p, dense, stream);
   if (p.head_dim == 128) return dense ? launch_one<128, true>(p, stream) : launch_one<128, false>(p, stream);
   return dense ? launch_one<64, true>(p, stream) : launch_one<64, false>(p, stream);
 }

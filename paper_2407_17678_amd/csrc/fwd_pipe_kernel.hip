@@ -17,12 +17,10 @@
 //     by the instruction's immediate offset).
 #include <hip/hip_runtime.h>
 
-#include <type_traits>
-#include <utility>
-
 #include "config.h"
 #include "device_util.h"
 #include "kernels.h"
+#include "sched_util.h"
 
 namespace s2 {
 
@@ -30,22 +28,6 @@ namespace {
 
 constexpr float kNegInf = -__builtin_inff();
 constexpr float kTau = 8.0f;  // log2 units a score may exceed the reference maximum by
-
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-
-#define S2_FENCE() __builtin_amdgcn_sched_barrier(0)
-#define S2_INLINE __attribute__((always_inline))
-
-// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a
-// compile-time constant in the body, whatever the optimiser's unrolling limits are
-template <int... I, class F>
-__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f) {
-  (f(std::integral_constant<int, I>{}), ...);
-}
-template <int N, class F>
-__device__ __forceinline__ void static_for(F&& f) {
-  static_for_impl(std::make_integer_sequence<int, N>{}, f);
-}
 
 template <int D, bool DENSE>
 __global__ __launch_bounds__(kThreads, 2) void fwd_pipe_kernel(const AttnParams p) {
@@ -184,10 +166,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_pipe_kernel(const AttnParams 
       // cannot promise for rows with one or two keys
       l_run += sc[g >> 1][r];
       if (i & 1) {
-        bf16x2 w;
-        w[0] = (__bf16)sc[g >> 1][r - 1];
-        w[1] = (__bf16)sc[g >> 1][r];
-        pb[g][i >> 1] = __builtin_bit_cast(uint32_t, w);
+        pb[g][i >> 1] = pack2(sc[g >> 1][r - 1], sc[g >> 1][r]);
       }
     }
   };
@@ -272,11 +251,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_pipe_kernel(const AttnParams 
   // maximum already covers them.
   auto step = [&](int it, f32x16 (&sc)[2], f32x16 (&sn)[2]) S2_INLINE {
     const int par = it & 1;
-#if !defined(S2_EXP) || S2_EXP < 6
     chunk_at(it + 2, kv0_nn, act_nn);
-#else
-    kv0_nn = 0; act_nn = it + 2 < total;
-#endif
     const uint16_t* kg = kb + (int64_t)kv0_nn * p.kv_st;  // K(it+2) -> the stage K(it) was in
     const uint16_t* vg = vb + (int64_t)kv0_n * p.kv_st;   // V(it+1) -> the stage V(it-1) was in
     const uint16_t* ks = sk[par ^ 1];
@@ -305,11 +280,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_pipe_kernel(const AttnParams 
       // NQK + NPV slots, one MFMA each
       static_for<NQK + NPV>([&](auto slc) S2_INLINE {
         constexpr int sl = decltype(slc)::value;
-#if !defined(S2_EXP) || S2_EXP < 4
         if constexpr (sl + kLead < NQK + NPV) frag_load(sl + kLead, ks, vs, fr);
-#else
-        if constexpr (sl == 0) frag_load(kLead, ks, vs, fr);
-#endif
         if constexpr (sl < NQK)
           qk_mfma(sl, sn, fr);
         else
@@ -325,31 +296,21 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_pipe_kernel(const AttnParams 
         // Nothing to execute: ties the running sum and maximum to this slot, or the optimiser
         // collects their additions and comparisons after the last MFMA.
         asm volatile("" : "+v"(l_run), "+v"(mx));
-#if !defined(S2_EXP) || S2_EXP < 2
         if constexpr (sl < 2 * NG) dma(std::integral_constant<int, sl>{});
-#endif
         S2_FENCE();
       });
       mc = mc_keep;
-#if !defined(S2_EXP) || S2_EXP < 5
       finish_scores(sn, kv0_n, act_n, mask_next, mx);
-#else
-      l_run += mx;
-#endif
     } else {
       static_for<2 * NG>([&](auto dc) S2_INLINE { dma(dc); });
     }
-#if !defined(S2_EXP) || S2_EXP < 6
     if (!DENSE) (void)list.get(min(it + 1, total - 1) >> cpb_sh, lane);  // keeps the entry window moving
-#endif
     kv0_c = kv0_n;
     act_c = act_n;
     kv0_n = kv0_nn;
     act_n = act_nn;
-#if !defined(S2_EXP) || S2_EXP < 3
     wait_all_loads();
     __syncthreads();
-#endif
   };
 
   int it = 0;

@@ -74,13 +74,16 @@ struct DecodeParams {
 hipError_t launch_fwd(const AttnParams& p, bool dense, hipStream_t stream);
 // The forward's fast path (head_dim 128, mask blocks of 64 or 128 tokens, whole 128-row tiles):
 // whether it covers a call, and its launch.  launch_fwd uses it where it applies.
-bool fwd64_applies(const AttnParams& p, bool dense);
-hipError_t launch_fwd64(const AttnParams& p, bool dense, hipStream_t stream);
 bool fwd_pipe_applies(const AttnParams& p, bool dense);
 hipError_t launch_fwd_pipe(const AttnParams& p, bool dense, hipStream_t stream);
 // `stages` selects which of the three backward launches run: 1 = delta, 2 = dK/dV, 4 = dQ.
 constexpr int kBwdDelta = 1, kBwdDkDv = 2, kBwdDq = 4, kBwdAll = 7;
 hipError_t launch_bwd(const AttnParams& p, bool dense, int stages, hipStream_t stream);
+// The dQ launch's fast path (head_dim 128, mask blocks of 64 or 128 tokens, whole 128-row tiles of a
+// fixed-length batch; it also leaves delta and base-2 LSE in the workspace): whether it covers a call,
+// and its launch.  launch_bwd uses it where it applies.
+bool dq_pipe_applies(const AttnParams& p, bool dense);
+hipError_t launch_dq_pipe(const AttnParams& p, bool dense, hipStream_t stream);
 hipError_t launch_decode(const DecodeParams& p, hipStream_t stream);
 
 }  // namespace s2

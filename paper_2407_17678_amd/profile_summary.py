@@ -1,0 +1,78 @@
+"""Turns rocprofv3 counter output into the short summaries kept under profiles/.
+
+    python -m paper_2407_17678_amd.profile_summary traffic WORKLOAD FETCH_CSV WRITE_CSV
+
+reads the two `*counter_collection.csv` files of
+
+    rocprofv3 --pmc FETCH_SIZE --output-format csv -d DIR -o p -- python3 bench.py --workload WORKLOAD \
+        --no-cpu-baseline --no-dense --no-extra --no-ceilings --steps 3 --warmup 1 --copy-calibration
+    rocprofv3 --pmc WRITE_SIZE ... (same command)
+
+and prints profiles/traffic_WORKLOAD.txt: HBM bytes per launch of each kernel of this library
+(FETCH_SIZE and WRITE_SIZE are in KiB per dispatch; each is scaled by what the same counter reads
+for the 1 GiB device-to-device copy that --copy-calibration runs first), headed by a fingerprint of
+the kernel sources, which bench.py checks before it reports the figures.
+"""
+
+import collections
+import csv
+import hashlib
+import os
+import re
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+
+
+def source_fingerprint():
+    """Hash of everything the kernels are compiled from."""
+    h = hashlib.sha1()
+    for name in sorted(os.listdir(CSRC)):
+        if name.endswith((".hip", ".h", ".cpp")):
+            h.update(name.encode())
+            with open(os.path.join(CSRC, name), "rb") as f:
+                h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def _per_kernel(path, counter):
+    """kernel short name -> mean counter value per dispatch; also the copy kernels' mean."""
+    sums = collections.defaultdict(list)
+    copies = []
+    with open(path) as f:
+        for r in csv.DictReader(f):
+            if r["Counter_Name"] != counter:
+                continue
+            name, val = r["Kernel_Name"], float(r["Counter_Value"])
+            m = re.search(r"s2::.*?(\w+_kernel)<", name)
+            if m:
+                sums[m.group(1)].append(val)
+            elif "copy" in name.lower() and val > 1e5:   # the calibration copy (1 GiB), not small housekeeping copies
+                copies.append(val)
+    return {k: sum(v) / len(v) for k, v in sums.items()}, (sum(copies) / len(copies) if copies else None)
+
+
+def traffic(workload, fetch_csv, write_csv):
+    fetch, fcopy = _per_kernel(fetch_csv, "FETCH_SIZE")
+    write, wcopy = _per_kernel(write_csv, "WRITE_SIZE")
+    if not fcopy or not wcopy:
+        raise SystemExit("no calibration copy found: run bench.py with --copy-calibration under the profiler")
+    gib_kib = float(1 << 20)
+    fs, ws = gib_kib / fcopy, gib_kib / wcopy   # scale factors: the copy reads and writes 1 GiB
+    lines = ["# sources %s" % source_fingerprint(),
+             "# kernel  HBM bytes per launch (read + written); rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on bench.py "
+             "--workload %s, scaled by %.2f / %.2f (1 GiB copy calibration)" % (workload, fs, ws)]
+    for k in sorted(set(fetch) | set(write)):
+        rd, wr = fetch.get(k, 0.0) * fs * 1024.0, write.get(k, 0.0) * ws * 1024.0
+        lines.append("%s %d   # read %d written %d" % (k, round(rd + wr), round(rd), round(wr)))
+    return "\n".join(lines) + "\n"
+
+
+if __name__ == "__main__":
+    if len(sys.argv) == 5 and sys.argv[1] == "traffic":
+        sys.stdout.write(traffic(sys.argv[2], sys.argv[3], sys.argv[4]))
+    elif len(sys.argv) == 2 and sys.argv[1] == "fingerprint":
+        print(source_fingerprint())
+    else:
+        raise SystemExit(__doc__)

@@ -81,7 +81,10 @@ def test_varlen_custom_pattern():
     assert np.abs(G.to_f64(lse) - LSE).max() <= LSE_TOL
 
 
-def test_varlen_rows_equal_the_fixed_length_forward_bit_for_bit():
+def test_varlen_rows_agree_with_the_fixed_length_forward():
+    # The two entry points may run differently scheduled kernels (the fixed-length one has a fast
+    # path for whole 128-row tiles), so they agree to rounding, not bit for bit: O within one bf16
+    # ulp of each other (and 1e-2), LSE within 1e-5.
     # each sequence on its own through s2_attn_fwd (lengths it accepts: whole blocks)
     w = dataclasses.replace(synth.WORKLOADS["1p3b_8k"], block_size=64, local_blocks=2, stride=3)
     H, Bk, S = 3, 12, 64
@@ -96,8 +99,9 @@ def test_varlen_rows_equal_the_fixed_length_forward_bit_for_bit():
         lse1 = torch.empty((1, H, L), dtype=torch.float32, device="cuda")
         B.s2_attn_fwd(lay, qs, ks, vs, o1, lse1, w.scale)
         torch.cuda.synchronize()
-        assert torch.equal(o1, o[:, :, lo:lo + L]), sq
-        assert torch.equal(lse1[0], lse[:, lo:lo + L]), sq
+        a, b = G.to_f64(o1), G.to_f64(o[:, :, lo:lo + L])
+        assert (np.abs(a - b) <= np.maximum(1e-2, 2.0 ** -7 * np.abs(b))).all(), sq
+        assert np.abs(G.to_f64(lse1[0]) - G.to_f64(lse[:, lo:lo + L])).max() <= 1e-5, sq
 
 
 def test_varlen_length_above_the_stated_maximum_is_cut_there():
