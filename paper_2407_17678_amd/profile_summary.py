@@ -8,6 +8,9 @@ reads the two `*counter_collection.csv` files of
         --no-cpu-baseline --no-dense --no-extra --no-ceilings --steps 3 --warmup 1 --copy-calibration
     rocprofv3 --pmc WRITE_SIZE ... (same command)
 
+(also: `kernels STATS_CSV` prints the per-kernel table of a --kernel-trace --stats run, `counters
+COUNTER_CSV` the mean of every counter per kernel, `fingerprint` the hash of the kernel sources)
+
 and prints profiles/traffic_WORKLOAD.txt: HBM bytes per launch of each kernel of this library
 (FETCH_SIZE and WRITE_SIZE are in KiB per dispatch; each is scaled by what the same counter reads
 for the 1 GiB device-to-device copy that --copy-calibration runs first), headed by a fingerprint of
@@ -48,9 +51,10 @@ def _per_kernel(path, counter):
             m = re.search(r"s2::.*?(\w+_kernel)<", name)
             if m:
                 sums[m.group(1)].append(val)
-            elif "copy" in name.lower() and val > 1e5:   # the calibration copy (1 GiB), not small housekeeping copies
+            elif "copyBuffer" in name:   # the runtime's device-to-device copy kernel
                 copies.append(val)
-    return {k: sum(v) / len(v) for k, v in sums.items()}, (sum(copies) / len(copies) if copies else None)
+    # the calibration copy (1 GiB) is the largest device-to-device copy of the run
+    return {k: sum(v) / len(v) for k, v in sums.items()}, (max(copies) if copies else None)
 
 
 def traffic(workload, fetch_csv, write_csv):
@@ -69,8 +73,40 @@ def traffic(workload, fetch_csv, write_csv):
     return "\n".join(lines) + "\n"
 
 
+def kernel_stats(stats_csv):
+    """Markdown table rows from a `*kernel_stats.csv` of rocprofv3 --kernel-trace --stats."""
+    out = ["| kernel | calls | avg ms | min ms | max ms | % of GPU time |", "|---|---|---|---|---|---|"]
+    with open(stats_csv) as f:
+        for r in csv.DictReader(f):
+            m = re.search(r"(\w+_kernel<[^>]*>)", r["Name"])
+            if m:
+                out.append("| %s | %s | %.3f | %.3f | %.3f | %s |" % (
+                    m.group(1), r["Calls"], float(r["AverageNs"]) / 1e6, float(r["MinNs"]) / 1e6,
+                    float(r["MaxNs"]) / 1e6, r["Percentage"]))
+    return "\n".join(out) + "\n"
+
+
+def counters(counter_csv):
+    """Mean value per dispatch of every counter in a `*counter_collection.csv`, per kernel of this library."""
+    agg = collections.defaultdict(lambda: collections.defaultdict(list))
+    with open(counter_csv) as f:
+        for r in csv.DictReader(f):
+            m = re.search(r"s2::.*?(\w+_kernel<[^>]*>)", r["Kernel_Name"])
+            if m:
+                agg[m.group(1)][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    out = []
+    for k, c in sorted(agg.items()):
+        out.append("%s (%d dispatches): %s" % (k, len(next(iter(c.values()))),
+                                               ", ".join("%s %.4g" % (n, sum(v) / len(v)) for n, v in sorted(c.items()))))
+    return "\n".join(out) + "\n"
+
+
 if __name__ == "__main__":
-    if len(sys.argv) == 5 and sys.argv[1] == "traffic":
+    if len(sys.argv) == 3 and sys.argv[1] == "kernels":
+        sys.stdout.write(kernel_stats(sys.argv[2]))
+    elif len(sys.argv) == 3 and sys.argv[1] == "counters":
+        sys.stdout.write(counters(sys.argv[2]))
+    elif len(sys.argv) == 5 and sys.argv[1] == "traffic":
         sys.stdout.write(traffic(sys.argv[2], sys.argv[3], sys.argv[4]))
     elif len(sys.argv) == 2 and sys.argv[1] == "fingerprint":
         print(source_fingerprint())

@@ -36,7 +36,7 @@ def _check_forward_rows(w, o, lse, bits, heads, rng):
         assert np.abs(gl - LSE).max() <= 1e-3, (b, h)
 
 
-def _check_backward_head(w, out, bits, b, h):
+def _check_backward_head(w, out, bits, b, h, stripe_columns=False):
     qb, kb, vb, gb = bits
     S = w.block_size
     M = orc.block_mask(w.heads, w.seqlen // S, w.local_blocks, w.stride)
@@ -48,6 +48,17 @@ def _check_backward_head(w, out, bits, b, h):
         e = G.rel_l2(G.to_f64(out[n][b, h]), ref)
         print("   %s head (%d,%d) rel-L2 %.3e" % (n, b, h, e), flush=True)
         assert e <= 2e-2, (n, b, h, e)
+    if stripe_columns and w.stride > 0:
+        # The key blocks on this head's stripes are attended by every later query block: their dK / dV
+        # rows come from the longest key tiles (hundreds of steps) and are a small part of the head's
+        # norm, so they are held to the bound on their own as well.
+        nb = w.seqlen // S
+        cols = np.arange(h % w.stride, nb, w.stride)
+        rows = (cols[:, None] * S + np.arange(S)[None, :]).ravel()
+        for n, ref in (("dk", dK), ("dv", dV)):
+            e = G.rel_l2(G.to_f64(out[n][b, h])[rows], ref[rows])
+            print("   %s head (%d,%d) stripe columns rel-L2 %.3e" % (n, b, h, e), flush=True)
+            assert e <= 2e-2, (n, b, h, e)
 
 
 def test_1p3b_8k_full():
@@ -56,9 +67,10 @@ def test_1p3b_8k_full():
     bits = synth.train_inputs(w)
     out = G.run_fwd_bwd(w, *bits)
     rng = np.random.default_rng(1)
-    _check_forward_rows(w, out["o"], out["lse"], bits[:3], [(0, 0), (1, 5), (2, 7), (3, 15)], rng)
-    for (b, h) in [(0, 0), (3, 15), (1, 6)]:
-        _check_backward_head(w, out, bits, b, h)
+    _check_forward_rows(w, out["o"], out["lse"], bits[:3], [(b, (5 * b + 2 * k) % w.heads) for b in range(w.batch) for k in range(2)], rng)
+    for b in range(w.batch):          # every (batch, head) pair: under a second of oracle each
+        for h in range(w.heads):
+            _check_backward_head(w, out, bits, b, h, stripe_columns=(h % 5 == 0))
     # every output finite and nothing left unwritten
     for n in ("o", "dq", "dk", "dv"):
         assert torch.isfinite(out[n].float()).all()
@@ -70,9 +82,9 @@ def test_7b_32k_full():
     bits = synth.train_inputs(w)
     out = G.run_fwd_bwd(w, *bits)
     rng = np.random.default_rng(2)
-    _check_forward_rows(w, out["o"], out["lse"], bits[:3], [(0, h) for h in (0, 5, 15, 16, 31)], rng)
-    for h in (0, 21, 31):   # smallest and largest stripe offsets and one between; about ten seconds of oracle each
-        _check_backward_head(w, out, bits, 0, h)
+    _check_forward_rows(w, out["o"], out["lse"], bits[:3], [(0, h) for h in (0, 3, 5, 10, 15, 16, 21, 26, 31)], rng)
+    for h in (0, 5, 15, 16, 21, 31):   # both ends of the stripe offsets and between; about ten seconds of oracle each
+        _check_backward_head(w, out, bits, 0, h, stripe_columns=True)
     for n in ("o", "dq", "dk", "dv"):
         assert torch.isfinite(out[n].float()).all()
 
@@ -85,7 +97,7 @@ def test_7b_128k_forward_full():
     qb, kb, vb = (synth.normal_bf16(rngs, shape) for _ in range(3))
     o, lse, _, _ = G.run_fwd(w, qb, kb, vb)
     rng = np.random.default_rng(3)
-    _check_forward_rows(w, o, lse, (qb, kb, vb), [(0, h) for h in (0, 7, 31)], rng)
+    _check_forward_rows(w, o, lse, (qb, kb, vb), [(0, h) for h in (0, 4, 7, 13, 18, 22, 27, 31)], rng)
     assert torch.isfinite(o.float()).all()
 
 
