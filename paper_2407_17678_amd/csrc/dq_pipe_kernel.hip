@@ -45,7 +45,7 @@ __global__ __launch_bounds__(kThreads, 2) void dq_pipe_kernel(const AttnParams p
   constexpr int NG = Tile::kGroups;
   constexpr int RB = Tile::kStride * 2;  // bytes per tile row
   constexpr int kSlots = 3 * KK;         // MFMAs (and fragments) per half step
-  constexpr int kLead = 5, kRing = kLead + 1;
+  constexpr int kLead = 5, kRing = kLead + 1;  // (3 to 7 measure the same)
   static_assert(D == 128, "the slot schedule below is laid out for head_dim 128");
   static_assert(KK == 8 && DT == 4, "24 slots per half chunk");
 
@@ -158,6 +158,8 @@ __global__ __launch_bounds__(kThreads, 2) void dq_pipe_kernel(const AttnParams p
       if (kbase + 8 * (r >> 2) + 4 * half + (r & 3) > qpos) s2[r] = kNegInf;
   };
 
+  bool act_cur = false;  // whether the half whose P is in sc[parity] is mine
+
   // ------------------------------------------------------------------ prologue
   wait_all_loads();
   __syncthreads();
@@ -174,6 +176,7 @@ __global__ __launch_bounds__(kThreads, 2) void dq_pipe_kernel(const AttnParams p
       sc[0] = mfma32(__builtin_bit_cast(bf16x8, lds_read16(k_row, 32 * kk)), qf[kk], sc[0]);
       dp = mfma32(__builtin_bit_cast(bf16x8, lds_read16(v_row, 32 * kk)), gf[kk], dp);
     }
+    act_cur = act;
     if (diag) mask_diag(sc[0], kv0_c);
     const float l0 = act ? lse_l : __builtin_inff();
 #pragma unroll
@@ -188,6 +191,16 @@ __global__ __launch_bounds__(kThreads, 2) void dq_pipe_kernel(const AttnParams p
     constexpr int KTN = KT ^ 1;  // which half of its chunk the next half is
     bool act_n, diag_n;
     half_state(kvn, keep_nx, KTN, act_n, diag_n);
+    // Neither this half nor the next is mine (mask row drops them, or their keys lie after my
+    // queries): nothing to compute; the next half's P and dP are zero.  One of the two being mine
+    // runs the whole stream (the other's probabilities are zero through lse = +inf).
+    const bool act_this = act_cur;
+    act_cur = act_n;
+    if (!act_this && !act_n) {
+      sc[PAR ^ 1] = f32x16{};
+      dp = f32x16{};
+      return;
+    }
     uint32_t k_row = lds_addr(sm.k[stn]) + l32 * RB + 16 * half + 32 * KTN * RB;
     uint32_t v_row = lds_addr(sm.v[stn]) + l32 * RB + 16 * half + 32 * KTN * RB;
     uint32_t k_tr = lds_addr(sm.k[stc]) + 2 * trb + 32 * KT * RB;
