@@ -566,6 +566,9 @@ def main():
                                      "random operands with two wavefronts per SIMD, alone and with a softmax's vector "
                                      "work per MFMA beside it; a pure 2 GiB read")
         roof["frac_of_measured_mfma"] = roof["achieved"] / ceilings["mfma_bf16_tflops"]
+        if extra is not None:
+            for name in ("7b_decode", "7b_decode_paged"):
+                extra[name]["frac_of_measured_read"] = extra[name]["hbm_gbs"] / ceilings["hbm_read_gbs"]
     out = {
         "metric": "effective sparse-attn TFLOP/s fwd+bwd (% MFMA peak) + speedup vs dense causal"
                   if with_bwd else "effective sparse-attn TFLOP/s fwd (% MFMA peak) + speedup vs dense causal",

@@ -8,7 +8,8 @@ reads the two `*counter_collection.csv` files of
         --no-cpu-baseline --no-dense --no-extra --no-ceilings --steps 3 --warmup 1 --copy-calibration
     rocprofv3 --pmc WRITE_SIZE ... (same command)
 
-(also: `kernels STATS_CSV` prints the per-kernel table of a --kernel-trace --stats run, `counters
+(also: `kernels STATS_CSV` prints the per-kernel table of a --kernel-trace --stats run, `trace
+TRACE_CSV` the same per kernel and grid size from the per-dispatch trace, `counters
 COUNTER_CSV` the mean of every counter per kernel, `fingerprint` the hash of the kernel sources)
 
 and prints profiles/traffic_WORKLOAD.txt: HBM bytes per launch of each kernel of this library
@@ -86,6 +87,22 @@ def kernel_stats(stats_csv):
     return "\n".join(out) + "\n"
 
 
+def kernel_trace(trace_csv):
+    """Markdown table from a `*kernel_trace.csv` of rocprofv3 --kernel-trace: this library's kernels by
+    name AND grid size, which tells the workloads of one bench.py run apart (each has its own grid)."""
+    agg = collections.defaultdict(list)
+    with open(trace_csv) as f:
+        for r in csv.DictReader(f):
+            m = re.search(r"s2::.*?(\w+_kernel<[^>]*>)", r["Kernel_Name"])
+            if m:
+                wg = int(r["Workgroup_Size_X"])
+                agg[(m.group(1), int(r["Grid_Size_X"]) // wg)].append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e6)
+    out = ["| kernel | workgroups | launches | avg ms | min ms | max ms |", "|---|---|---|---|---|---|"]
+    for (k, g), v in sorted(agg.items(), key=lambda kv: -sum(kv[1])):
+        out.append("| %s | %d | %d | %.3f | %.3f | %.3f |" % (k, g, len(v), sum(v) / len(v), min(v), max(v)))
+    return "\n".join(out) + "\n"
+
+
 def counters(counter_csv):
     """Mean value per dispatch of every counter in a `*counter_collection.csv`, per kernel of this library."""
     agg = collections.defaultdict(lambda: collections.defaultdict(list))
@@ -104,6 +121,8 @@ def counters(counter_csv):
 if __name__ == "__main__":
     if len(sys.argv) == 3 and sys.argv[1] == "kernels":
         sys.stdout.write(kernel_stats(sys.argv[2]))
+    elif len(sys.argv) == 3 and sys.argv[1] == "trace":
+        sys.stdout.write(kernel_trace(sys.argv[2]))
     elif len(sys.argv) == 3 and sys.argv[1] == "counters":
         sys.stdout.write(counters(sys.argv[2]))
     elif len(sys.argv) == 5 and sys.argv[1] == "traffic":
