@@ -106,6 +106,15 @@ def measured_ceilings():
     ms = time_events(rd, 10, 2)
     out["hbm_read_gbs"] = (2 << 30) / (ms * 1e-3) / 1e9
     del src
+    # what accumulating partial gradients with atomics would cost (a single-pass backward's dQ)
+    acc = torch.zeros(128 << 20, dtype=torch.float32, device="cuda")
+    added = [0.0]
+
+    def at():
+        added[0] = B.s2_probe_atomic_add(acc)
+    ms = time_events(at, 3, 1)
+    out["fp32_atomic_add_gbs"] = added[0] / (ms * 1e-3) / 1e9
+    del acc
     torch.cuda.empty_cache()
     return out
 
@@ -564,7 +573,7 @@ def main():
         log("[bench] measured ceilings: %s" % ceilings)
         roof["measured_peak"] = dict(ceilings, note="the library's probe kernels timed in this run: a pure MFMA loop on "
                                      "random operands with two wavefronts per SIMD, alone and with a softmax's vector "
-                                     "work per MFMA beside it; a pure 2 GiB read")
+                                     "work per MFMA beside it; a pure 2 GiB read; coalesced fp32 atomic adds into a 512 MiB buffer")
         roof["frac_of_measured_mfma"] = roof["achieved"] / ceilings["mfma_bf16_tflops"]
         if extra is not None:
             for name in ("7b_decode", "7b_decode_paged"):

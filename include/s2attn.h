@@ -332,6 +332,11 @@ int s2_layout_resident_blocks(const s2_layout* layout, int32_t head, int32_t len
  * `iters` trips of 8 each, optionally with a softmax's vector work per MFMA beside them; *flops
  * receives the flops of the launch.  s2_probe_read: reads `bytes` (16-byte aligned) once.
  * Errors: NULL, BAD_PARAM (iters), ALIGN, HIP. */
+/* s2_probe_atomic_add: 8192 workgroups add 64 tiles of 32 x 128 floats each into buf (DEVICE, fp32,
+ * `bytes` long, at least 1 MiB, 16-byte aligned; its contents are added to) with coalesced fp32
+ * atomic adds; *bytes_added receives the bytes of the launch.  It measures what accumulating
+ * partial gradients with atomics costs.  Errors: NULL, ALIGN, BAD_PARAM, HIP. */
+int s2_probe_atomic_add(void* buf, size_t bytes, void* stream, double* bytes_added);
 size_t s2_probe_scratch_bytes(void);
 int s2_probe_mfma(int32_t with_vector_work, int32_t iters, void* scratch, void* stream, double* flops);
 int s2_probe_read(const void* src, size_t bytes, void* scratch, void* stream);

@@ -84,7 +84,7 @@ EXPORTS = (
     "s2_attn_bwd_workspace_bytes", "s2_attn_bwd_stages", "s2_dense_causal_fwd", "s2_dense_causal_bwd", "s2_attn_decode",
     "s2_attn_decode_workspace_bytes", "s2_attn_decode_default_splits", "s2_attn_decode_static", "s2_attn_decode_paged",
     "s2_kv_resident_blocks", "s2_attn_decode_layout", "s2_attn_decode_paged_layout",
-    "s2_layout_resident_blocks", "s2_probe_scratch_bytes", "s2_probe_mfma", "s2_probe_read", "s2_status_string",
+    "s2_layout_resident_blocks", "s2_probe_scratch_bytes", "s2_probe_mfma", "s2_probe_read", "s2_probe_atomic_add", "s2_status_string",
     "s2_last_hip_error", "s2_version",
 )
 
@@ -140,6 +140,7 @@ def lib():
     L.s2_probe_scratch_bytes.restype = C.c_size_t
     L.s2_probe_mfma.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(C.c_double)]
     L.s2_probe_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+    L.s2_probe_atomic_add.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_double)]
     L.s2_status_string.argtypes = [C.c_int]
     L.s2_status_string.restype = C.c_char_p
     L.s2_last_hip_error.restype = C.c_int
@@ -446,3 +447,11 @@ def s2_probe_read(src, scratch, stream=None):
     nbytes = src.numel() * src.element_size()
     _check(lib().s2_probe_read(_ptr(src), nbytes, _ptr(scratch), _stream_ptr(stream)), "s2_probe_read")
     return nbytes
+
+
+def s2_probe_atomic_add(buf, stream=None):
+    """Enqueues the fp32 atomic-add probe on `buf` (a float32 device tensor); returns the bytes added."""
+    added = C.c_double(0.0)
+    _check(lib().s2_probe_atomic_add(_ptr(buf), buf.numel() * buf.element_size(), _stream_ptr(stream),
+                                     C.byref(added)), "s2_probe_atomic_add")
+    return added.value

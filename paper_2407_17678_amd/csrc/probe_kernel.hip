@@ -7,6 +7,8 @@
 //     higher), alone or with the vector work of a softmax per MFMA beside it (one multiply-add,
 //     one exponential, one add, half a conversion, half a maximum).
 //   * HBM: a grid-stride read of a buffer with 16-byte loads.
+//   * fp32 atomic adds to global memory, coalesced (what accumulating dQ partials in a single-pass
+//     backward would cost: the reason this library's backward is two launches without atomics).
 #include <hip/hip_runtime.h>
 
 #include "../../include/s2attn.h"
@@ -92,6 +94,22 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const u32x4* src, size_
   out[blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// Coalesced fp32 atomic adds, the way a single-pass backward would accumulate dQ partials: each
+// workgroup adds 16 KB tiles (32 rows x 128 floats) into a [rows x 128] buffer, the tiles of
+// concurrent workgroups apart, later ones revisiting rows as other key tiles would.
+__global__ __launch_bounds__(256) void probe_atomic_kernel(float* buf, uint32_t tiles, int tiles_per_wg) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int t = 0; t < tiles_per_wg; ++t) {
+    const uint32_t tile = (uint32_t)(((uint64_t)blockIdx.x * 131u + (uint64_t)t * 977u) % tiles);
+    float* base = buf + (size_t)tile * 32 * 128;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+        atomicAdd(base + (size_t)(wave * 8 + 2 * r + (lane >> 5)) * 128 + 32 * dt + (lane & 31), 1.0f);
+  }
+}
+
 constexpr int kProbeGrid = 512;  // two workgroups of four wavefronts per compute unit
 
 }  // namespace
@@ -122,6 +140,18 @@ int s2_probe_read(const void* src, size_t bytes, void* scratch, void* stream) {
   // enough workgroups to cover every compute unit several times over
   hipLaunchKernelGGL(s2::probe_read_kernel, dim3(4096), dim3(256), 0, static_cast<hipStream_t>(stream),
                      static_cast<const s2::u32x4*>(src), bytes / 16, static_cast<uint32_t*>(scratch));
+  return hipGetLastError() == hipSuccess ? S2_OK : S2_ERR_HIP;
+}
+
+int s2_probe_atomic_add(void* buf, size_t bytes, void* stream, double* bytes_added) {
+  if (!buf || !bytes_added) return S2_ERR_NULL;
+  if (bytes < (1u << 20) || (reinterpret_cast<uintptr_t>(buf) & 15u) != 0) return S2_ERR_ALIGN;
+  const uint64_t tiles = bytes / 16384;
+  if (tiles > 0xffffffffu) return S2_ERR_BAD_PARAM;
+  const int wgs = 8192, per_wg = 64;
+  hipLaunchKernelGGL(s2::probe_atomic_kernel, dim3(wgs), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<float*>(buf), (uint32_t)tiles, per_wg);
+  *bytes_added = (double)wgs * per_wg * 16384.0;
   return hipGetLastError() == hipSuccess ? S2_OK : S2_ERR_HIP;
 }
 

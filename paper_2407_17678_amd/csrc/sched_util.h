@@ -11,8 +11,9 @@
 //     18.6 ns with two wavefronts and nothing else to do: 1.8 PFLOP/s for the chip, 72 % of the
 //     2.5 PFLOP/s that 2.4 GHz would give; with the softmax's vector work beside it 21.2 ns;
 //   * a lone wavefront on a SIMD issues at most one instruction per 4 cycles of whatever kind, and a
-//     scalar ALU instruction between vector ones costs it about 10 cycles: its schedules keep
-//     scalar work out of the loop; a second wavefront on the SIMD hides all of that;
+//     scalar ALU instruction between vector ones costs it about 10 cycles; a second wavefront on
+//     the SIMD hides all of that, which is why these kernels run two per SIMD (forms with one
+//     wavefront per SIMD, 64 rows each and all 512 registers, were built and measured slower);
 //   * back-to-back MFMAs into the same accumulator run at full rate.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -37,47 +38,6 @@ __device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>
 template <int N, class F>
 __device__ __forceinline__ void static_for(F&& f) {
   static_for_impl(std::make_integer_sequence<int, N>{}, f);
-}
-
-// MFMAs as inline assembly, for kernels that run one wavefront per SIMD with all 512 registers:
-// the compiler would put EVERY MFMA result of such a kernel into the accumulation registers and
-// copy it out for each vector instruction; written this way each accumulator sits in the register
-// file it belongs to.  The compiler does not see through them, so the wait states the hardware
-// needs between an MFMA and a vector instruction that reads its result (11 for this 8-pass MFMA),
-// and between a vector instruction and an MFMA that reads its result (2), are the caller's
-// business: mfma_result_fence / mfma_operand_fence below.
-// d (vector registers) = a x b
-__device__ __forceinline__ void mfma_vz(f32x16& d, u32x4 a, u32x4 b) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "v"(b));
-}
-// d (vector registers) += a x b
-__device__ __forceinline__ void mfma_v(f32x16& d, u32x4 a, u32x4 b) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "v"(b));
-}
-// the same with b in accumulation registers
-__device__ __forceinline__ void mfma_vz_ab(f32x16& d, u32x4 a, u32x4 b) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
-}
-__device__ __forceinline__ void mfma_v_ab(f32x16& d, u32x4 a, u32x4 b) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
-}
-// d (accumulation registers) += a x b
-__device__ __forceinline__ void mfma_a(f32x16& d, u32x4 a, u32x4 b) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(d) : "v"(a), "v"(b));
-}
-// 12 wait states after the MFMAs that wrote d, before vector instructions read it
-__device__ __forceinline__ void mfma_result_fence(f32x16& d) { asm volatile("s_nop 7\n\ts_nop 3" : "+v"(d)); }
-__device__ __forceinline__ void mfma_result_fence(f32x16& d0, f32x16& d1) {
-  asm volatile("s_nop 7\n\ts_nop 3" : "+v"(d0), "+v"(d1));
-}
-// 2 wait states after the vector instructions that wrote b, before an MFMA reads it
-__device__ __forceinline__ void mfma_operand_fence(u32x4& b) { asm volatile("s_nop 1" : "+v"(b)); }
-__device__ __forceinline__ void mfma_operand_fence(u32x4& b0, u32x4& b1) { asm volatile("s_nop 1" : "+v"(b0), "+v"(b1)); }
-
-// 16 bytes from global memory straight into accumulation registers (complete after s_waitcnt vmcnt(0);
-// the compiler does not track it)
-__device__ __forceinline__ void load_to_agpr(u32x4& dst, const void* src) {
-  asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(dst) : "v"(src));
 }
 
 // LDS reads at (32-bit LDS byte address held in a register) + (compile-time byte offset): the hand

@@ -40,3 +40,10 @@ def test_read_probe_rate():
     src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 255)
     gbs = (1 << 30) / _time(lambda: B.s2_probe_read(src, scratch)) / 1e9
     assert 1000 < gbs < 8200, gbs
+
+
+def test_atomic_add_probe_adds_what_it_says():
+    buf = torch.zeros(4 << 20, dtype=torch.float32, device="cuda")   # 16 MiB = 1024 tiles
+    added = B.s2_probe_atomic_add(buf)
+    torch.cuda.synchronize()
+    assert float(buf.double().sum().item()) * 4 == added   # every add is 1.0f on a 4-byte element
