@@ -538,6 +538,39 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
   }
 
   if (!wave_active || (VARLEN && kvw0 + l32 >= N)) return;
+  if (!VARLEN && CH == 64) {
+    // Whole rows exist: dK and dV go out through LDS (free since the loop's last barrier; each
+    // wavefront uses regions of its own, so no barrier).  A lane holds its row's features four at a
+    // time, and storing them from there touches 32 rows per instruction with 16 bytes each; read back
+    // 16 bytes per lane, row after row, an instruction stores four whole rows.
+    constexpr int RS = D + 8;  // staging row stride (elements)
+    static_assert(4 * 32 * (D + 8) <= 2 * DmaTile<D, CH>::kElems || CH != 64, "the staging rows fit two stages");
+    uint16_t* sk_ = &sm.q[0][0] + wave * 32 * RS;
+    uint16_t* sv_ = &sm.g[0][0] + wave * 32 * RS;
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 wk, wv;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          wk[e] = (__bf16)(acc_dk[dt][4 * g + e] * p.scale);
+          wv[e] = (__bf16)(acc_dv[dt][4 * g + e]);
+        }
+        *reinterpret_cast<bf16x4*>(sk_ + l32 * RS + 32 * dt + 8 * g + 4 * half) = wk;
+        *reinterpret_cast<bf16x4*>(sv_ + l32 * RS + 32 * dt + 8 * g + 4 * half) = wv;
+      }
+    uint16_t* dk_base = p.dk + kv_off + (int64_t)kvw0 * p.kv_st;
+    uint16_t* dv_base = p.dv + kv_off + (int64_t)kvw0 * p.kv_st;
+    constexpr int PPR = D / 8, RPI = 64 / PPR;  // 16-byte pieces per row, rows per instruction
+#pragma unroll
+    for (int i = 0; i < 32 / RPI; ++i) {
+      const int r = RPI * i + lane / PPR, piece = lane % PPR;
+      *reinterpret_cast<u32x4*>(dk_base + (int64_t)r * p.kv_st + 8 * piece) = *reinterpret_cast<const u32x4*>(sk_ + r * RS + 8 * piece);
+      *reinterpret_cast<u32x4*>(dv_base + (int64_t)r * p.kv_st + 8 * piece) = *reinterpret_cast<const u32x4*>(sv_ + r * RS + 8 * piece);
+    }
+    return;
+  }
   uint16_t* dk_row = p.dk + kv_off + (int64_t)(kvw0 + l32) * p.kv_st;
   uint16_t* dv_row = p.dv + kv_off + (int64_t)(kvw0 + l32) * p.kv_st;
 #pragma unroll

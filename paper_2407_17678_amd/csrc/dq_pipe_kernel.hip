@@ -283,7 +283,13 @@ __global__ __launch_bounds__(kThreads, 2) void dq_pipe_kernel(const AttnParams p
   }
 
   // ------------------------------------------------------------------ epilogue
-  uint16_t* row = p.dq + q_off + (int64_t)my_row * p.q_st;
+  // dQ = scale * acc goes out through LDS (free since the loop's last barrier; each wavefront uses a
+  // region of its own, so no barrier): a lane holds its row's features four at a time, and storing
+  // them from there would touch 32 rows per instruction with 16 bytes each; read back 16 bytes per
+  // lane, row after row, an instruction stores four whole rows.
+  constexpr int RS = D + 8;  // staging row stride (elements)
+  uint16_t* stage = sm.k[0] + wave * MW * RS;
+  static_assert(4 * MW * RS <= 2 * Tile::kElems, "the staging rows fit the K stages");
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -291,8 +297,15 @@ __global__ __launch_bounds__(kThreads, 2) void dq_pipe_kernel(const AttnParams p
       bf16x4 w;
 #pragma unroll
       for (int e = 0; e < 4; ++e) w[e] = (__bf16)(acc[dt][4 * g + e] * p.scale);
-      *reinterpret_cast<bf16x4*>(row + 32 * dt + 8 * g + 4 * half) = w;
+      *reinterpret_cast<bf16x4*>(stage + l32 * RS + 32 * dt + 8 * g + 4 * half) = w;
     }
+  uint16_t* obase = p.dq + q_off + (int64_t)qw0 * p.q_st;
+#pragma unroll
+  for (int i = 0; i < MW / 4; ++i) {
+    const int r = 4 * i + (lane >> 4), piece = lane & 15;
+    const u32x4 x = *reinterpret_cast<const u32x4*>(stage + r * RS + 8 * piece);
+    *reinterpret_cast<u32x4*>(obase + (int64_t)r * p.q_st + 8 * piece) = x;
+  }
 }
 
 // A kernel's dynamic LDS limit is a per-device attribute: remember, per device, that it is set.

@@ -321,10 +321,15 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_pipe_kernel(const AttnParams 
   if (it < total) step(it, s[0], s[1]);
 
   // ------------------------------------------------------------------ epilogue
+  // O = acc / l goes out through LDS (free since the loop's last barrier; each wavefront uses a
+  // region of its own, so no barrier): a lane holds its row's features four at a time, and storing
+  // them from there would touch 32 rows per instruction with 16 bytes each; read back 16 bytes per
+  // lane, row after row, an instruction stores four whole rows.
   const float l_tot = sum_halves(l_run);
   const float inv = 1.0f / l_tot;
-  const int qrow = ql0 + l32;
-  uint16_t* orow = p.o + q_off + (int64_t)qrow * p.q_st;
+  constexpr int RS = D + 8;  // staging row stride (elements): 8-byte writes of a row group spread over the banks
+  uint16_t* stage = sk[0] + wave * MW * RS;
+  static_assert(4 * MW * RS <= 2 * Tile::kElems, "the staging rows fit the K stages");
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -332,9 +337,16 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_pipe_kernel(const AttnParams 
       bf16x4 w;
 #pragma unroll
       for (int e = 0; e < 4; ++e) w[e] = (__bf16)(acc[dt][4 * g + e] * inv);
-      *reinterpret_cast<bf16x4*>(orow + 32 * dt + 8 * g + 4 * half) = w;
+      *reinterpret_cast<bf16x4*>(stage + l32 * RS + 32 * dt + 8 * g + 4 * half) = w;
     }
-  if (half == 0) p.lse[((int64_t)b * p.heads + h) * p.q_rows + qrow] = m_ref * p.scale + __logf(l_tot);
+  uint16_t* obase = p.o + q_off + (int64_t)ql0 * p.q_st;
+#pragma unroll
+  for (int i = 0; i < MW / 4; ++i) {
+    const int r = 4 * i + (lane >> 4), piece = lane & 15;
+    const u32x4 x = *reinterpret_cast<const u32x4*>(stage + r * RS + 8 * piece);
+    *reinterpret_cast<u32x4*>(obase + (int64_t)r * p.q_st + 8 * piece) = x;
+  }
+  if (half == 0) p.lse[((int64_t)b * p.heads + h) * p.q_rows + ql0 + l32] = m_ref * p.scale + __logf(l_tot);
 }
 
 }  // namespace
