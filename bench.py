@@ -138,6 +138,11 @@ def bench_train(w, steps, warmup, with_dense=True, with_bwd=True, dense_steps=3,
     t0 = time.time()
     lay = B.s2_layout_build(B.layout_params(H, N // S, S, w.local_blocks, w.stride, 0, w.window_blocks, 0))
     layout_ms = (time.time() - t0) * 1e3
+    # The backward has two forms, chosen by the workspace the caller brings: the small one (delta and
+    # LSE only: the dQ launch recomputes S and dP) and, where it applies, the one that also holds dS
+    # between the dK/dV and dQ launches (2 bytes per kept block element; nothing is computed twice).
+    keep_bytes = B.s2_attn_bwd_layout_workspace_bytes(lay, Bt, H, N, D) if with_bwd else 0
+    ws_keep = torch.empty(keep_bytes, dtype=torch.uint8, device="cuda") if keep_bytes > ws.numel() else None
     nnz = B.s2_layout_get(lay)["nnz"]
     # KV-block loads of the forward: one per list entry of a merged 128-row query tile, against one
     # per kept block of every S-token mask row without merging (the reload accounting of section 3.2)
@@ -146,8 +151,10 @@ def bench_train(w, steps, warmup, with_dense=True, with_bwd=True, dense_steps=3,
     dense_pairs = H * N * (N + 1) // 2 * Bt
 
     fwd = lambda: B.s2_attn_fwd(lay, q, k, v, o, lse, w.scale)
-    bwd = lambda: B.s2_attn_bwd(lay, q, k, v, o, lse, g, dq, dk, dv, w.scale, ws)
-    stage = lambda s: (lambda: B.s2_attn_bwd_stages(lay, q, k, v, o, lse, g, dq, dk, dv, w.scale, ws, s))
+    bwd_of = lambda wsp: (lambda: B.s2_attn_bwd(lay, q, k, v, o, lse, g, dq, dk, dv, w.scale, wsp))
+    stage_of = lambda wsp, s: (lambda: B.s2_attn_bwd_stages(lay, q, k, v, o, lse, g, dq, dk, dv, w.scale, wsp, s))
+    bwd = bwd_of(ws)
+    stage = lambda s: stage_of(ws, s)
 
     def step():
         fwd()
@@ -165,11 +172,25 @@ def bench_train(w, steps, warmup, with_dense=True, with_bwd=True, dense_steps=3,
     res["ms_fwd"] = time_events(fwd, steps, 1)
     flops_fwd = 4.0 * D * pairs
     if with_bwd:
-        # the backward is the dQ launch (which also computes delta) followed by the dK/dV launch
-        res["ms_bwd_dq"] = time_events(stage(B.BWD_DQ), steps, 1)
-        res["ms_bwd_dkdv"] = time_events(stage(B.BWD_DKDV), steps, 1)
-        # the stand-alone delta kernel, only used when dK/dV is asked for without dQ: not in a step
+        # small workspace: the dQ launch (which also computes delta) followed by the dK/dV launch
+        rec = dict(ms_dq=time_events(stage(B.BWD_DQ), steps, 1), ms_dkdv=time_events(stage(B.BWD_DKDV), steps, 1),
+                   ms=time_events(bwd, steps, 1), workspace_bytes=ws.numel())
+        res["backward_recomputing"] = rec
+        res["backward_path"] = "recomputing"
+        # the stand-alone delta kernel (with the small workspace only used when dK/dV is asked for without dQ)
         res["ms_delta_standalone"] = time_events(stage(B.BWD_DELTA), steps, 1)
+        res["ms_bwd_dq"], res["ms_bwd_dkdv"], res["ms_bwd_delta"] = rec["ms_dq"], rec["ms_dkdv"], 0.0
+        if ws_keep is not None:
+            # larger workspace: delta kernel, dK/dV launch that leaves dS, dQ = dS K
+            keep = dict(ms_delta=time_events(stage_of(ws_keep, B.BWD_DELTA), steps, 1),
+                        ms_dkdv=time_events(stage_of(ws_keep, B.BWD_DKDV), steps, 1),
+                        ms_dq=time_events(stage_of(ws_keep, B.BWD_DQ), steps, 1),
+                        ms=time_events(bwd_of(ws_keep), steps, 1), workspace_bytes=ws_keep.numel())
+            res["backward_keeping_ds"] = keep
+            if keep["ms"] < rec["ms"]:   # a step uses the faster form, as a caller with the memory to spare would
+                bwd = bwd_of(ws_keep)
+                res["backward_path"] = "keeping dS"
+                res["ms_bwd_dq"], res["ms_bwd_dkdv"], res["ms_bwd_delta"] = keep["ms_dq"], keep["ms_dkdv"], keep["ms_delta"]
         flops = 14.0 * D * pairs
     else:
         flops = flops_fwd
@@ -241,7 +262,8 @@ def bench_train(w, steps, warmup, with_dense=True, with_bwd=True, dense_steps=3,
     kernels = {"fwd_pipe_kernel" if fast else "fwd_kernel": (res["ms_fwd"], 4.0)}
     if with_bwd:
         kernels["dkdv_kernel"] = (res["ms_bwd_dkdv"], 8.0)
-        kernels["dq_pipe_kernel" if fast else "dq_kernel"] = (res["ms_bwd_dq"], 2.0)
+        dq_name = "dq_gemm_kernel" if res["backward_path"] == "keeping dS" else "dq_pipe_kernel" if fast else "dq_kernel"
+        kernels[dq_name] = (res["ms_bwd_dq"], 2.0)
     dom = max(kernels, key=lambda n: kernels[n][0])
     ach = kernels[dom][1] * D * pairs / (kernels[dom][0] * 1e-3) / 1e12
     res["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
@@ -249,9 +271,10 @@ def bench_train(w, steps, warmup, with_dense=True, with_bwd=True, dense_steps=3,
                        "avg_launch_ms": kernels[dom][0],
                        "algorithmic_flops_per_launch": kernels[dom][1] * D * pairs}
     if with_bwd:
-        # The attribution above is a convention (the dQ launch recomputes S and dP, which it is not
-        # credited with); the whole backward against its 10 * D * pairs says what the two launches deliver.
-        t_bwd = res["ms_bwd_dq"] + res["ms_bwd_dkdv"]
+        # The attribution above is a convention (with the small workspace the dQ launch recomputes S and
+        # dP, which it is not credited with); the whole backward against its 10 * D * pairs says what
+        # the launches deliver together.
+        t_bwd = res["ms_bwd_dq"] + res["ms_bwd_dkdv"] + res["ms_bwd_delta"]
         res["roofline"]["whole_backward"] = {"ms": t_bwd, "achieved": 10.0 * D * pairs / (t_bwd * 1e-3) / 1e12,
                                              "frac": 10.0 * D * pairs / (t_bwd * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
         res["roofline"]["forward"] = {"ms": res["ms_fwd"], "achieved": res["tflops_fwd"],

@@ -173,8 +173,11 @@ int s2_layout_get(const s2_layout* layout, s2_layout_view* out);
  * tile keeps block unit*blocks_per_unit + c.  Row tiles (which = S2_TILES_FWD, S2_TILES_DQ): member
  * r is block row t*group + r, partners are KV block columns, ascending.  Column tiles
  * (S2_TILES_DKDV): member r is block column members[(h*T + t)*group + r] (-1 = none), partners are
- * query block rows, descending.  order[h*T + k] is the k-th tile of head h by descending length.
- * Errors: NULL, BAD_PARAM (which). */
+ * query block rows, descending - except that where a head has eight or more column tiles of one
+ * length n, each attending one unbroken run of rows (the local-window tiles), such a tile starts at
+ * its row that is a multiple of n and goes down from there, wrapping round to the run's last row, so
+ * that tiles running side by side read the same query block at the same time.  order[h*T + k] is the
+ * k-th tile of head h by descending length.  Errors: NULL, BAD_PARAM (which). */
 enum { S2_TILES_FWD = 0, S2_TILES_DQ = 1, S2_TILES_DKDV = 2 };
 typedef struct {
   const int32_t* ptr;      /* [H*T + 1]                              */
@@ -186,6 +189,24 @@ typedef struct {
   int32_t blocks_per_unit; /* 1, or 2 with 16-token blocks           */
 } s2_tile_view;
 int s2_layout_get_tiles(const s2_layout* layout, int which, s2_tile_view* out);
+
+/* Where the backward that keeps dS (see s2_attn_bwd_layout_workspace_bytes) puts it, for inspection.
+ * The dK/dV launch walks the S2_TILES_DKDV lists in 64-row chunks (an entry of a 128-token block is
+ * two chunks, the later rows first); chunk c of entry e of the `ent` array is step e * cpb + c
+ * (cpb = block_size / 64) and leaves two 8 KiB units of 64 queries x 64 keys: 2 * step + r for the
+ * keys of member r (64-token blocks) or of the block's 64-key half r (128-token blocks).  dq_units
+ * says where the dQ launch finds them again: for chunk c (64 keys, ascending) of entry e of the
+ * S2_TILES_DQ `ent` array and 64-row half m of the 128-row query tile, dq_units[(e * cpb + c) * 2 + m]
+ * is the unit, or -1 when mask row m does not keep the block or every key of the piece lies after
+ * every query.  count = entries of dq_units, ds_units = units per batch element; both 0 when the
+ * layout's block size is not 64 or 128 (the path does not apply).  HOST pointers into the handle.
+ * Errors: NULL. */
+typedef struct {
+  const int32_t* dq_units; /* [count]                                */
+  int64_t count;
+  int64_t ds_units;
+} s2_ds_units_view;
+int s2_layout_get_ds_units(const s2_layout* layout, s2_ds_units_view* out);
 
 /* ---- forward (section 3.2: softmax over the kept keys only) ------------------------------ */
 
@@ -228,6 +249,18 @@ int s2_attn_bwd(const s2_layout* layout, const s2_tensors* t, float scale, void*
                 size_t workspace_bytes, void* stream);
 size_t s2_attn_bwd_workspace_bytes(int32_t batch, int32_t heads, int32_t seqlen, int32_t head_dim);
 
+/* The larger workspace with which s2_attn_bwd / s2_attn_bwd_stages compute nothing twice.  With the
+ * size above, the dQ launch forms the scores and dP = dO V^T a second time to get at
+ * dS = P * (dP - delta): seven contractions for the five the gradient consists of.  Given this many
+ * bytes instead, the dK/dV launch leaves dS (bf16, 2 bytes per kept block element: 8 KiB per 64 x 64
+ * piece the launch visits) in the workspace and the dQ launch is the single contraction
+ * dQ = scale * dS K over it.  Same results to rounding (dQ then takes the same bf16 dS that dK takes),
+ * bitwise repeatable like the other path.  Covers head_dim 128, mask blocks of 64 or 128 tokens and
+ * seqlen a multiple of 128; for any other call the value equals s2_attn_bwd_workspace_bytes and the
+ * other path runs.  Which path a call takes is decided by workspace_bytes alone. */
+size_t s2_attn_bwd_layout_workspace_bytes(const s2_layout* layout, int32_t batch, int32_t heads,
+                                          int32_t seqlen, int32_t head_dim);
+
 /* The backward for a packed batch of sequences of different lengths: the gradient of
  * s2_attn_fwd_varlen, same tensors and cu_seqlens (o and lse as that call left them), d_o / dq /
  * dk / dv packed like q / k / v.  Rows that belong to no sequence are left as they were.
@@ -243,7 +276,10 @@ size_t s2_attn_bwd_varlen_workspace_bytes(int32_t heads, int32_t rows, int32_t h
  * (an OR of the flags below) so that a profiler or a benchmark can time each launch on its own;
  * with S2_BWD_ALL it is s2_attn_bwd.  S2_BWD_DKDV needs delta in the workspace: from S2_BWD_DQ in
  * the same or an earlier call, or from S2_BWD_DELTA, a stand-alone delta kernel that only runs
- * when S2_BWD_DQ is not part of the call.  Errors as s2_attn_bwd, plus BAD_PARAM for stages. */
+ * when S2_BWD_DQ is not part of the call.  With the larger workspace of
+ * s2_attn_bwd_layout_workspace_bytes the order is delta kernel (S2_BWD_DELTA), dK/dV (S2_BWD_DKDV,
+ * needs delta, leaves dS), dQ (S2_BWD_DQ, needs dS from S2_BWD_DKDV in the same or an earlier call
+ * on the same workspace).  Errors as s2_attn_bwd, plus BAD_PARAM for stages. */
 enum { S2_BWD_DELTA = 1, S2_BWD_DKDV = 2, S2_BWD_DQ = 4, S2_BWD_ALL = 7 };
 int s2_attn_bwd_stages(const s2_layout* layout, const s2_tensors* t, float scale, void* workspace,
                        size_t workspace_bytes, int stages, void* stream);

@@ -52,6 +52,10 @@ class TileView(C.Structure):
                 ("blocks_per_unit", C.c_int32)]
 
 
+class DsUnitsView(C.Structure):
+    _fields_ = [("dq_units", C.POINTER(C.c_int32)), ("count", C.c_int64), ("ds_units", C.c_int64)]
+
+
 class Tensors(C.Structure):
     _fields_ = [("q", C.c_void_p), ("k", C.c_void_p), ("v", C.c_void_p), ("o", C.c_void_p),
                 ("lse", C.c_void_p), ("d_o", C.c_void_p), ("dq", C.c_void_p), ("dk", C.c_void_p),
@@ -79,9 +83,9 @@ class PagedDecodeArgs(C.Structure):
 
 
 EXPORTS = (
-    "s2_layout_build", "s2_layout_from_csr", "s2_layout_destroy", "s2_layout_get", "s2_layout_get_tiles", "s2_attn_fwd", "s2_attn_fwd_rows", "s2_attn_fwd_varlen", "s2_attn_bwd_varlen",
+    "s2_layout_build", "s2_layout_from_csr", "s2_layout_destroy", "s2_layout_get", "s2_layout_get_tiles", "s2_layout_get_ds_units", "s2_attn_fwd", "s2_attn_fwd_rows", "s2_attn_fwd_varlen", "s2_attn_bwd_varlen",
     "s2_attn_bwd_varlen_workspace_bytes", "s2_attn_bwd",
-    "s2_attn_bwd_workspace_bytes", "s2_attn_bwd_stages", "s2_dense_causal_fwd", "s2_dense_causal_bwd", "s2_attn_decode",
+    "s2_attn_bwd_workspace_bytes", "s2_attn_bwd_layout_workspace_bytes", "s2_attn_bwd_stages", "s2_dense_causal_fwd", "s2_dense_causal_bwd", "s2_attn_decode",
     "s2_attn_decode_workspace_bytes", "s2_attn_decode_default_splits", "s2_attn_decode_static", "s2_attn_decode_paged",
     "s2_kv_resident_blocks", "s2_attn_decode_layout", "s2_attn_decode_paged_layout",
     "s2_layout_resident_blocks", "s2_probe_scratch_bytes", "s2_probe_mfma", "s2_probe_read", "s2_probe_atomic_add", "s2_status_string",
@@ -105,6 +109,7 @@ def lib():
     L.s2_layout_destroy.argtypes = [C.c_void_p]
     L.s2_layout_get.argtypes = [C.c_void_p, C.POINTER(LayoutView)]
     L.s2_layout_get_tiles.argtypes = [C.c_void_p, C.c_int, C.POINTER(TileView)]
+    L.s2_layout_get_ds_units.argtypes = [C.c_void_p, C.POINTER(DsUnitsView)]
     L.s2_attn_fwd.argtypes = [C.c_void_p, C.POINTER(Tensors), C.c_float, C.c_void_p]
     L.s2_attn_fwd_rows.argtypes = [C.c_void_p, C.POINTER(Tensors), C.c_int32, C.c_int32, C.c_float, C.c_void_p]
     L.s2_attn_fwd_varlen.argtypes = [C.c_void_p, C.POINTER(Tensors), C.c_void_p, C.c_int32, C.c_int32, C.c_float,
@@ -118,6 +123,8 @@ def lib():
                                      C.c_int, C.c_void_p]
     L.s2_attn_bwd_workspace_bytes.argtypes = [C.c_int32] * 4
     L.s2_attn_bwd_workspace_bytes.restype = C.c_size_t
+    L.s2_attn_bwd_layout_workspace_bytes.argtypes = [C.c_void_p] + [C.c_int32] * 4
+    L.s2_attn_bwd_layout_workspace_bytes.restype = C.c_size_t
     L.s2_dense_causal_fwd.argtypes = [C.POINTER(Tensors), C.c_float, C.c_void_p]
     L.s2_dense_causal_bwd.argtypes = [C.POINTER(Tensors), C.c_float, C.c_void_p, C.c_size_t, C.c_void_p]
     L.s2_attn_decode.argtypes = [C.POINTER(LayoutParams), C.POINTER(DecodeArgs), C.c_float, C.c_void_p,
@@ -239,6 +246,14 @@ def s2_layout_get_tiles(layout, which):
             "blocks_per_unit": v.blocks_per_unit}
 
 
+def s2_layout_get_ds_units(layout):
+    """Host copy of the unit table of the backward that keeps dS (see s2_ds_units_view in the header)."""
+    v = DsUnitsView()
+    _check(lib().s2_layout_get_ds_units(layout.handle, C.byref(v)), "s2_layout_get_ds_units")
+    units = np.ctypeslib.as_array(v.dq_units, shape=(v.count,)).copy() if v.count else np.zeros(0, np.int32)
+    return {"dq_units": units, "ds_units": int(v.ds_units)}
+
+
 def bf16_bits_to_device(bits, device="cuda"):
     """uint16 bf16 bit patterns (numpy) -> torch.bfloat16 tensor on the GPU holding the same bits."""
     import torch
@@ -297,6 +312,10 @@ def s2_attn_bwd_varlen(layout, q, k, v, o, lse, d_o, dq, dk, dv, cu_seqlens, max
 
 def s2_attn_bwd_workspace_bytes(batch, heads, seqlen, head_dim):
     return lib().s2_attn_bwd_workspace_bytes(batch, heads, seqlen, head_dim)
+
+
+def s2_attn_bwd_layout_workspace_bytes(layout, batch, heads, seqlen, head_dim):
+    return lib().s2_attn_bwd_layout_workspace_bytes(layout.handle, batch, heads, seqlen, head_dim)
 
 
 def s2_attn_bwd(layout, q, k, v, o, lse, d_o, dq, dk, dv, scale, workspace, stream=None):

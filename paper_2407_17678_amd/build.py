@@ -14,7 +14,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libs2attn.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
-SOURCES = ["api.hip", "layout.cpp", "fwd_kernel.hip", "fwd_pipe_kernel.hip", "bwd_kernel.hip", "dq_pipe_kernel.hip", "decode_kernel.hip", "probe_kernel.hip"]
+SOURCES = ["api.hip", "layout.cpp", "fwd_kernel.hip", "fwd_pipe_kernel.hip", "bwd_kernel.hip", "dq_pipe_kernel.hip", "dq_gemm_kernel.hip", "decode_kernel.hip", "probe_kernel.hip"]
 
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function"]
 # gfx950 only.  Packed-fp32 VALU forms are switched off for the device pass (the host pass

@@ -51,7 +51,8 @@ void free_device_copies(s2_layout* L) {
   free_tiles(L->kv_tiles);
   if (L->d_row_ptr) (void)hipFree(L->d_row_ptr);
   if (L->d_col_idx) (void)hipFree(L->d_col_idx);
-  L->d_row_ptr = L->d_col_idx = nullptr;
+  if (L->d_dq_units) (void)hipFree(L->d_dq_units);
+  L->d_row_ptr = L->d_col_idx = L->d_dq_units = nullptr;
 }
 
 s2::DevTiles dev_tiles(const s2::TileList& t) {
@@ -176,6 +177,7 @@ int finish_layout(s2_layout* L, int st, s2_layout** out) {
       s2::build_tiles(*L, s2::kFwdBM / S, false, L->fwd_tiles);
       s2::build_tiles(*L, s2::kBwdBM / S, false, L->q_tiles);
       s2::build_tiles(*L, s2::kBwdBN / S, true, L->kv_tiles);
+      s2::build_ds_units(*L);
     } catch (const std::bad_alloc&) {
       st = S2_ERR_OVERFLOW;
     }
@@ -189,7 +191,7 @@ int finish_layout(s2_layout* L, int st, s2_layout** out) {
     int dev = 0;
     bool ok = hip_ok(hipGetDevice(&dev)) && upload_tiles(L->fwd_tiles) && upload_tiles(L->q_tiles) &&
               upload_tiles(L->kv_tiles) && upload(L->row_ptr, &L->d_row_ptr) &&
-              upload(L->col_idx, &L->d_col_idx);
+              upload(L->col_idx, &L->d_col_idx) && upload(L->dq_units, &L->d_dq_units);
     if (!ok) {
       free_device_copies(L);
       delete L;
@@ -271,6 +273,14 @@ int s2_layout_get_tiles(const s2_layout* L, int which, s2_tile_view* out) {
   return S2_OK;
 }
 
+int s2_layout_get_ds_units(const s2_layout* L, s2_ds_units_view* out) {
+  if (!L || !out) return S2_ERR_NULL;
+  out->dq_units = L->dq_units.data();
+  out->count = (int64_t)L->dq_units.size();
+  out->ds_units = L->ds_units;
+  return S2_OK;
+}
+
 int s2_attn_fwd(const s2_layout* layout, const s2_tensors* t, float scale, void* stream) {
   if (!layout) return S2_ERR_NULL;
   int st = check_tensors(t, false, scale);
@@ -292,6 +302,22 @@ size_t s2_attn_bwd_workspace_bytes(int32_t batch, int32_t heads, int32_t seqlen,
   const size_t rows = (size_t)batch * heads * seqlen;
   // delta = rowsum(dO * O) and a copy of LSE in base-2 units, 256-byte aligned each
   return 2 * (((rows * sizeof(float) + 255) / 256) * 256);
+}
+
+namespace {
+// The backward that keeps dS covers head_dim 128, mask blocks of 64 or 128 tokens (the layout then
+// carries the unit table) and whole 128-row tiles.
+bool keeps_ds(const s2_layout* L, int32_t seqlen, int32_t head_dim) {
+  return L->ds_units > 0 && head_dim == 128 && seqlen % s2::kBwdBM == 0 &&
+         (int64_t)seqlen == (int64_t)L->p.num_blocks * L->p.block_size;
+}
+}  // namespace
+
+size_t s2_attn_bwd_layout_workspace_bytes(const s2_layout* layout, int32_t batch, int32_t heads, int32_t seqlen,
+                                          int32_t head_dim) {
+  const size_t small = s2_attn_bwd_workspace_bytes(batch, heads, seqlen, head_dim);
+  if (!layout || small == 0 || heads != layout->p.num_heads || !keeps_ds(layout, seqlen, head_dim)) return small;
+  return small + (size_t)batch * (size_t)layout->ds_units * 8192;
 }
 
 int s2_attn_bwd(const s2_layout* layout, const s2_tensors* t, float scale, void* workspace,
@@ -404,6 +430,14 @@ int s2_attn_bwd_stages(const s2_layout* layout, const s2_tensors* t, float scale
   p.fwd_tiles = dev_tiles(layout->fwd_tiles);
   p.q_tiles = dev_tiles(layout->q_tiles);
   p.kv_tiles = dev_tiles(layout->kv_tiles);
+  // a workspace large enough to keep dS selects the backward that computes nothing twice
+  const size_t small = s2_attn_bwd_workspace_bytes(t->batch, t->heads, t->seqlen, t->head_dim);
+  if (keeps_ds(layout, t->seqlen, t->head_dim) &&
+      workspace_bytes >= s2_attn_bwd_layout_workspace_bytes(layout, t->batch, t->heads, t->seqlen, t->head_dim)) {
+    p.ds_store = reinterpret_cast<uint16_t*>(static_cast<unsigned char*>(workspace) + small);
+    p.ds_units = layout->ds_units;
+    p.dq_units = layout->d_dq_units;
+  }
   return hip_ok(s2::launch_bwd(p, false, stages, static_cast<hipStream_t>(stream))) ? S2_OK : S2_ERR_HIP;
 }
 

@@ -303,7 +303,10 @@ struct DkvSmem {
 // the whole layout, so the workgroup first drops out if none of them exists in its sequence, skips
 // the list entries (query blocks, last first) that lie after the sequence's end, clamps the loads
 // of the ragged last chunk and zeroes P and dS for the query rows of it that do not exist.
-template <int D, bool DENSE, int CH, bool VARLEN = false>
+// STORE: dS, rounded to bf16 as the dK contraction takes it, is also left in the workspace for the dQ
+// launch (launch_dq_gemm), 4 KiB per wavefront and step: [half chunk][16-query slab][key][lane half][8
+// queries in the order the lane holds them], i.e. each B operand as it is, 1 KiB per store instruction.
+template <int D, bool DENSE, int CH, bool VARLEN = false, bool STORE = false>
 __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
   typedef DmaTile<D, CH> Tile;
   constexpr int QT = CH / 32;
@@ -368,6 +371,10 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
     n_ent = p.kv_tiles.ptr[h * T + tile + 1] - ent_lo;
   }
   const int total = n_ent * cpb;
+  // where this wavefront's dS of step 0 goes: unit 2 * (global step) + wave / 2, its keys' half of it
+  uint16_t* ds_wave = nullptr;
+  if (STORE)
+    ds_wave = p.ds_store + ((int64_t)b * p.ds_units + (((int64_t)ent_lo << cpb_sh) * 2 + (wave >> 1))) * 4096 + (wave & 1) * 2048;
   EntryList list;
   if (!DENSE) list.init(p.kv_tiles.ent + ent_lo, n_ent, lane);
   // chunk `it` of the tile's list: its first row, and whether my mask row / column keeps it
@@ -406,9 +413,12 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
   // a wait for all outstanding loads when it is fetched back.
   auto issue_chunk = [&](int q0, int buf, int ln) {
     if (VARLEN && q0 + CH > N) {  // ragged end of the sequence: rows past it fetch its last row instead
-      const typename Tile::Plan pr = Tile::plan_rows(p.q_st, wave, ln, N - q0);
-      Tile::issue(pr, qb + (int64_t)q0 * p.q_st, sm.q[buf], wave);
-      Tile::issue(pr, gb + (int64_t)q0 * p.q_st, sm.g[buf], wave);
+      // (a list need not be in descending order, so a chunk that lies wholly after the sequence's end
+      // can turn up anywhere in it: it fetches the last row 64 times and nothing uses it)
+      const int qs = min(q0, N - 1);
+      const typename Tile::Plan pr = Tile::plan_rows(p.q_st, wave, ln, N - qs);
+      Tile::issue(pr, qb + (int64_t)qs * p.q_st, sm.q[buf], wave);
+      Tile::issue(pr, gb + (int64_t)qs * p.q_st, sm.g[buf], wave);
     } else {
       Tile::issue(plan, qb + (int64_t)q0 * p.q_st, sm.q[buf], wave);
       Tile::issue(plan, gb + (int64_t)q0 * p.q_st, sm.g[buf], wave);
@@ -417,10 +427,10 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
     // each, in one direct load issued by the wavefront that has one load fewer than the others in the two tiles
     constexpr int NL = CH / 4;  // lanes per array, 16 bytes each
     if (wave == 3 && ln < 2 * NL)
-      dma16(delta_b + q0, 16 * ln + (ln < NL ? 0u : stats_gap - 16u * NL), lds_addr(&sm.rs[buf]));
+      dma16(delta_b + (VARLEN && q0 >= N ? 0 : q0), 16 * ln + (ln < NL ? 0u : stats_gap - 16u * NL), lds_addr(&sm.rs[buf]));
   };
-  // first step: a packed sequence skips the chunks of query blocks that lie after its end (the list
-  // starts at the layout's last row)
+  // first step: a packed sequence skips the leading chunks of query blocks that lie after its end (most
+  // lists start at the layout's last row; such chunks further on are walked without being used)
   int it0 = 0;
   if (VARLEN) {
     for (; it0 < total; ++it0) {
@@ -474,6 +484,8 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
       issue_chunk(q1, buf ^ 1, ln);
     }
 
+    int stores = 0;  // dS stores of this step (wave-uniform)
+    uint16_t* ds_step = STORE ? ds_wave + (int64_t)it * 8192 : nullptr;
     if (wave_active && keep && q0 + CH - 1 >= kvw0) {
       const uint16_t* qs = sm.q[buf];
       const uint16_t* gs = sm.g[buf];
@@ -524,6 +536,14 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
                                   s[8 * u + 5], s[8 * u + 6], s[8 * u + 7]);
           const bf16x8 dsb = pack8(dp[8 * u + 0], dp[8 * u + 1], dp[8 * u + 2], dp[8 * u + 3], dp[8 * u + 4],
                                    dp[8 * u + 5], dp[8 * u + 6], dp[8 * u + 7]);
+          if constexpr (STORE) {
+            const uint32_t off = 16u * (2 * l32 + half) + 1024u * (2 * qt + u);
+            // non-temporal: written once here and read by a later launch, it should not push the Q / dO
+            // blocks this kernel re-reads out of L2
+            __builtin_nontemporal_store(__builtin_bit_cast(u32x4, dsb),
+                                        reinterpret_cast<u32x4*>(reinterpret_cast<unsigned char*>(ds_step) + off));
+            ++stores;
+          }
 #pragma unroll
           for (int dt = 0; dt < D / 32; ++dt) {
             acc_dv[dt] = mfma32(Tile::tr_frag(gs, dt, 2 * qt + u, trb), pb, acc_dv[dt]);
@@ -533,7 +553,13 @@ __global__ __launch_bounds__(kThreads, 2) void dkdv_kernel(const AttnParams p) {
       }
     }
 
-    wait_all_loads();
+    // the next chunk has landed; this step's dS stores, issued after its loads, may stay in flight
+    if (STORE && stores == 4)
+      wait_loads_but<4>();
+    else if (STORE && stores == 2)
+      wait_loads_but<2>();
+    else
+      wait_all_loads();
     __syncthreads();
   }
 
@@ -617,6 +643,29 @@ hipError_t launch_one(const AttnParams& p, int stages, hipStream_t stream) {
 
   const int64_t rows = (int64_t)p.batch * p.heads * p.seqlen;
   constexpr int RPB = 256 / (D / 8);
+  const int bh = p.batch * p.heads;
+  if constexpr (D == 128 && !DENSE && CH == 64 && !VARLEN) {
+    if (p.ds_store) {
+      // The backward that keeps dS: delta, then dK/dV (5 contractions' worth of work less the dQ one,
+      // leaving dS in the workspace), then dQ = scale * dS K - nothing is computed twice.
+      static SmemSet store_set;
+      e = set_smem(&dkdv_kernel<D, false, CH, false, true>, sizeof(DkvSmem<D, CH>), store_set);
+      if (e != hipSuccess) return e;
+      if (stages & kBwdDelta) {
+        hipLaunchKernelGGL((delta_kernel<D>), dim3((unsigned)((rows + RPB - 1) / RPB)), dim3(256), 0, stream, p);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+      }
+      if (stages & kBwdDkDv) {
+        hipLaunchKernelGGL((dkdv_kernel<D, false, CH, false, true>), dim3(grid_for(bh, p.kv_tiles.tiles_per_head)),
+                           dim3(kThreads), sizeof(DkvSmem<D, CH>), stream, p);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+      }
+      if (stages & kBwdDq) e = launch_dq_gemm(p, stream);
+      return e;
+    }
+  }
   // The dQ kernel computes delta itself and leaves it (and LSE in base-2 units) in the workspace,
   // so it runs first and the stand-alone delta kernel only when dQ is not part of the call
   // (a packed batch is always a whole backward).
@@ -625,7 +674,6 @@ hipError_t launch_one(const AttnParams& p, int stages, hipStream_t stream) {
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  const int bh = p.batch * p.heads;
   if ((stages & kBwdDq) && !VARLEN && CH == 64 && dq_pipe_applies(p, DENSE)) {
     e = launch_dq_pipe(p, DENSE, stream);
     if (e != hipSuccess) return e;

@@ -281,6 +281,18 @@ __device__ __forceinline__ void wait_all_loads() {
   asm volatile("" ::: "memory");
 }
 
+// At most N of this wavefront's vector-memory operations are still outstanding.  The counter retires in
+// issue order, loads and stores alike, so this says that everything issued before the last N has landed
+// (direct loads included) without waiting for the last N themselves - stores whose completion nothing
+// in the kernel depends on, or loads that are a further step ahead.
+template <int N>
+__device__ __forceinline__ void wait_loads_but() {
+  static_assert(N >= 0 && N < 64, "the counter has six bits");
+  // vmcnt in bits 3:0 and 15:14; expcnt (bits 6:4) and lgkmcnt (bits 11:8) at their maxima: no wait
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+  asm volatile("" ::: "memory");
+}
+
 // A tile's entry list, held in registers: lane i of the wavefront keeps entry 64*b + i of the
 // current batch of 64 entries, and the next batch is fetched one batch ahead, so the main loops
 // read their block index with v_readlane instead of waiting on global memory every iteration.

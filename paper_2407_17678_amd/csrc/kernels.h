@@ -44,6 +44,13 @@ struct AttnParams {
   DevTiles fwd_tiles; // row tiles of the forward kernel -> KV blocks
   DevTiles q_tiles;   // row tiles of the dQ kernel -> KV blocks
   DevTiles kv_tiles;  // column tiles -> Q blocks
+  // Backward with dS kept (head_dim 128, mask blocks of 64 or 128 tokens): the dK/dV kernel leaves
+  // dS = P * (dP - delta), rounded to bf16, in the workspace, in units of 64 queries x 64 keys (8 KiB),
+  // unit (2 * step + wavefront pair) of its walk; the dQ launch is then the one contraction dS K over
+  // those units.  ds_store == nullptr: dS is not kept and the dQ kernel recomputes it.
+  uint16_t* ds_store;          // [batch][ds_units] units
+  int64_t ds_units;            // units per batch element
+  const int32_t* dq_units;     // [dQ list chunk][query half of the 128-row tile]: unit, -1 = none
 };
 
 struct DecodeParams {
@@ -84,6 +91,8 @@ hipError_t launch_bwd(const AttnParams& p, bool dense, int stages, hipStream_t s
 // and its launch.  launch_bwd uses it where it applies.
 bool dq_pipe_applies(const AttnParams& p, bool dense);
 hipError_t launch_dq_pipe(const AttnParams& p, bool dense, hipStream_t stream);
+// The dQ launch of the backward that keeps dS: dQ = scale * dS K over the stored units.
+hipError_t launch_dq_gemm(const AttnParams& p, hipStream_t stream);
 hipError_t launch_decode(const DecodeParams& p, hipStream_t stream);
 
 }  // namespace s2

@@ -191,6 +191,9 @@ int build_from_csr(int num_heads, int num_blocks, int block_size, const int32_t*
   return S2_OK;
 }
 
+// column tiles of one length that a head must have before they walk their rows in step (see below)
+constexpr int kRotateMinTiles = 8;
+
 void build_tiles(const s2_layout& L, int group, bool transpose, TileList& out) {
   // partner blocks per entry: the kernels walk partners in units of at least 32 tokens, so with
   // 16-token blocks an entry covers two of them
@@ -248,12 +251,94 @@ void build_tiles(const s2_layout& L, int group, bool transpose, TileList& out) {
       out.max_len = std::max(out.max_len, len);
       out.ptr[(size_t)h * T + t + 1] = (int32_t)out.ent.size();
     }
+    // ... except where many column tiles have the same length and each attends one unbroken run of
+    // rows: the local-window tiles, whose runs are shifted against each other by a tile's width.
+    // They are dispatched one after the other (equal lengths keep their index order below) and run
+    // side by side, and walking every run from its own end would have neighbours read the same Q / dO
+    // block several steps apart - by then it has left the L2.  Such a tile of n entries instead starts
+    // at its row that is a multiple of n and goes down from there, wrapping round to its last row: at
+    // any step, tiles of one length are at rows congruent modulo n, which for overlapping runs is the
+    // same row.
+    if (transpose) {
+      const int32_t* hp = out.ptr.data() + (size_t)h * T;
+      std::vector<int> same((size_t)out.max_len + 2, 0);
+      for (int t = 0; t < T; ++t) ++same[hp[t + 1] - hp[t]];
+      for (int t = 0; t < T; ++t) {
+        const int n = hp[t + 1] - hp[t];
+        if (n < 2 || same[n] < kRotateMinTiles) continue;
+        int32_t* e = out.ent.data() + hp[t];
+        const int top = e[0] >> 16, bottom = e[n - 1] >> 16;
+        if (top - bottom != n - 1) continue;  // not one unbroken run
+        std::rotate(e, e + (top - (top / n) * n), e + n);
+      }
+    }
     // heaviest tiles first inside the head, so the tail of a launch is made of short tiles
     int32_t* ord = out.order.data() + (size_t)h * T;
     std::iota(ord, ord + T, 0);
     const int32_t* hp = out.ptr.data() + (size_t)h * T;
     std::stable_sort(ord, ord + T, [&](int a, int b) { return hp[a + 1] - hp[a] > hp[b + 1] - hp[b]; });
   }
+}
+
+void build_ds_units(s2_layout& L) {
+  L.dq_units.clear();
+  L.ds_units = 0;
+  const int S = L.p.block_size;
+  if (S != 64 && S != 128) return;
+  const int sub = S / 64;  // 64-token pieces per block side = 64-row chunks per list entry
+  const int H = L.p.num_heads, B = L.p.num_blocks;
+  const TileList& kt = L.kv_tiles;
+  const TileList& qt = L.q_tiles;
+  if (kt.group != 128 / S || qt.group != 128 / S) return;
+  if ((int64_t)kt.ent.size() * sub * 2 > std::numeric_limits<int32_t>::max()) return;
+  // position of block (i, j) of head h in the compressed rows (it is there: both lists come from them)
+  auto csr_pos = [&](int h, int i, int j) -> int64_t {
+    const int32_t* lo = L.col_idx.data() + L.row_ptr[(size_t)h * B + i];
+    const int32_t* hi = L.col_idx.data() + L.row_ptr[(size_t)h * B + i + 1];
+    const int32_t* it = std::lower_bound(lo, hi, j);
+    return (it != hi && *it == j) ? (int64_t)(it - L.col_idx.data()) : -1;
+  };
+  // the dK/dV pass: which unit each 64 x 64 piece of a kept block goes to
+  std::vector<int32_t> unit_of((size_t)L.nnz * sub * sub, -1);
+  const int Tk = kt.tiles_per_head;
+  for (int h = 0; h < H; ++h)
+    for (int t = 0; t < Tk; ++t) {
+      const int32_t* mem = kt.members.data() + ((size_t)h * Tk + t) * kt.group;
+      for (int32_t eg = kt.ptr[(size_t)h * Tk + t]; eg < kt.ptr[(size_t)h * Tk + t + 1]; ++eg) {
+        const int e = kt.ent[(size_t)eg], partner = e >> 16;
+        for (int c = 0; c < sub; ++c) {
+          const int q64 = partner * sub + (sub - 1 - c);  // the pass walks an entry's chunks last first
+          for (int pair = 0; pair < 2; ++pair) {
+            const int member = sub == 1 ? pair : 0;
+            if (mem[member] < 0 || !((e >> member) & 1)) continue;
+            const int k64 = sub == 1 ? mem[member] : mem[0] * 2 + pair;
+            if (k64 > q64) continue;  // every key of the piece lies after every query: never computed
+            const int64_t n = csr_pos(h, q64 / sub, k64 / sub);
+            if (n < 0) continue;
+            unit_of[(size_t)n * sub * sub + (q64 % sub) * sub + k64 % sub] = (int32_t)(((int64_t)eg * sub + c) * 2 + pair);
+          }
+        }
+      }
+    }
+  // the dQ pass: where each chunk of its lists finds its two pieces
+  const int Tq = qt.tiles_per_head;
+  L.dq_units.assign(qt.ent.size() * sub * 2, -1);
+  for (int h = 0; h < H; ++h)
+    for (int t = 0; t < Tq; ++t)
+      for (int32_t eg = qt.ptr[(size_t)h * Tq + t]; eg < qt.ptr[(size_t)h * Tq + t + 1]; ++eg) {
+        const int e = qt.ent[(size_t)eg], j = e >> 16;
+        for (int c = 0; c < sub; ++c) {
+          const int k64 = j * sub + c;
+          for (int m = 0; m < 2; ++m) {
+            const int q64 = t * 2 + m, member = (m * 64) / S;
+            if (q64 / sub >= B || !((e >> member) & 1) || k64 > q64) continue;
+            const int64_t n = csr_pos(h, q64 / sub, j);
+            if (n < 0) continue;
+            L.dq_units[((size_t)eg * sub + c) * 2 + m] = unit_of[(size_t)n * sub * sub + (q64 % sub) * sub + k64 % sub];
+          }
+        }
+      }
+  L.ds_units = (int64_t)kt.ent.size() * sub * 2;
 }
 
 }  // namespace s2

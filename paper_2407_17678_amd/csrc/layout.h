@@ -49,6 +49,13 @@ struct s2_layout {
   s2::TileList fwd_tiles; // row groups  -> kept KV blocks   (forward)
   s2::TileList q_tiles;   // row groups  -> kept KV blocks   (dQ pass)
   s2::TileList kv_tiles;  // column groups -> attending Q blocks (dK/dV pass)
+  // Backward that keeps dS (64- and 128-token blocks): the dK/dV pass leaves dS in units of 64
+  // queries x 64 keys, unit (2 * step + wavefront pair) of its walk over kv_tiles; dq_units names, for
+  // every 64-key chunk of the q_tiles lists and either 64-row half of the query tile, the unit that
+  // holds it (-1: the mask row drops the block, or no pair of the piece is causal).
+  std::vector<int32_t> dq_units;
+  int32_t* d_dq_units = nullptr;
+  int64_t ds_units = 0;   // units per batch element (0: this layout does not support the path)
 };
 
 namespace s2 {
@@ -62,4 +69,6 @@ int build_from_csr(int num_heads, int num_blocks, int block_size, const int32_t*
 int64_t row_blocks(const s2_layout_params& p, int head, int i, int32_t* out, int64_t capacity);
 // Merge `group` consecutive rows (transpose=false) or columns (transpose=true).
 void build_tiles(const s2_layout& L, int group, bool transpose, TileList& out);
+// Fills dq_units / ds_units from q_tiles and kv_tiles (built before, with 128-row and 128-key tiles).
+void build_ds_units(s2_layout& L);
 }  // namespace s2

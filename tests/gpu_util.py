@@ -62,8 +62,10 @@ def oracle_mask(w, H, N, dense=False):
                           window_blocks=w.window_blocks, dense=dense)
 
 
-def run_fwd_bwd(w, qb, kb, vb, gb, dense=False):
-    """Library forward then backward; returns dict of device tensors."""
+def run_fwd_bwd(w, qb, kb, vb, gb, dense=False, keep_ds=False):
+    """Library forward then backward; returns dict of device tensors.  keep_ds: the workspace of
+    s2_attn_bwd_layout_workspace_bytes (filled with NaN patterns), which selects the backward that
+    keeps dS where it applies."""
     q, k, v, g = to_dev(qb), to_dev(kb), to_dev(vb), to_dev(gb)
     Bt, H, N, D = q.shape
     o = torch.empty_like(q)
@@ -76,7 +78,10 @@ def run_fwd_bwd(w, qb, kb, vb, gb, dense=False):
     else:
         lay = B.s2_layout_build(B.layout_params(H, N // w.block_size, w.block_size, w.local_blocks,
                                                 w.stride, 0, w.window_blocks, 0))
+        if keep_ds:
+            ws = torch.full((B.s2_attn_bwd_layout_workspace_bytes(lay, Bt, H, N, D),), 0xFF, dtype=torch.uint8,
+                            device="cuda")
         B.s2_attn_fwd(lay, q, k, v, o, lse, w.scale)
         B.s2_attn_bwd(lay, q, k, v, o, lse, g, dq, dk, dv, w.scale, ws)
     torch.cuda.synchronize()
-    return dict(o=o, lse=lse, dq=dq, dk=dk, dv=dv)
+    return dict(o=o, lse=lse, dq=dq, dk=dk, dv=dv, ws_bytes=ws.numel())

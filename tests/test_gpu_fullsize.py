@@ -36,57 +36,70 @@ def _check_forward_rows(w, o, lse, bits, heads, rng):
         assert np.abs(gl - LSE).max() <= 1e-3, (b, h)
 
 
-def _check_backward_head(w, out, bits, b, h, stripe_columns=False):
+def _check_backward_head(w, outs, bits, b, h, stripe_columns=False):
+    """`outs`: results of the two forms of the backward (small workspace: the dQ launch recomputes S
+    and dP; larger workspace: dS kept between the launches), both held to the oracle's one result."""
     qb, kb, vb, gb = bits
     S = w.block_size
     M = orc.block_mask(w.heads, w.seqlen // S, w.local_blocks, w.stride)
     f = lambda x: G.bits_f64(x[b, h])
     dQ, dK, dV, O, LSE = orc.attention_backward_head(f(qb), f(kb), f(vb), f(gb), M[h], S, w.scale)
-    assert G.o_excess(G.to_f64(out["o"][b, h]), O) <= 0
-    assert np.abs(G.to_f64(out["lse"][b, h]) - LSE).max() <= 1e-3
-    for n, ref in (("dq", dQ), ("dk", dK), ("dv", dV)):
-        e = G.rel_l2(G.to_f64(out[n][b, h]), ref)
-        print("   %s head (%d,%d) rel-L2 %.3e" % (n, b, h, e), flush=True)
-        assert e <= 2e-2, (n, b, h, e)
-    if stripe_columns and w.stride > 0:
-        # The key blocks on this head's stripes are attended by every later query block: their dK / dV
-        # rows come from the longest key tiles (hundreds of steps) and are a small part of the head's
-        # norm, so they are held to the bound on their own as well.
-        nb = w.seqlen // S
-        cols = np.arange(h % w.stride, nb, w.stride)
-        rows = (cols[:, None] * S + np.arange(S)[None, :]).ravel()
-        for n, ref in (("dk", dK), ("dv", dV)):
-            e = G.rel_l2(G.to_f64(out[n][b, h])[rows], ref[rows])
-            print("   %s head (%d,%d) stripe columns rel-L2 %.3e" % (n, b, h, e), flush=True)
-            assert e <= 2e-2, (n, b, h, e)
+    for which, out in outs.items():
+        assert G.o_excess(G.to_f64(out["o"][b, h]), O) <= 0
+        assert np.abs(G.to_f64(out["lse"][b, h]) - LSE).max() <= 1e-3
+        for n, ref in (("dq", dQ), ("dk", dK), ("dv", dV)):
+            e = G.rel_l2(G.to_f64(out[n][b, h]), ref)
+            print("   %s head (%d,%d) %s rel-L2 %.3e" % (n, b, h, which, e), flush=True)
+            assert e <= 2e-2, (which, n, b, h, e)
+        if stripe_columns and w.stride > 0:
+            # The key blocks on this head's stripes are attended by every later query block: their dK / dV
+            # rows come from the longest key tiles (hundreds of steps) and are a small part of the head's
+            # norm, so they are held to the bound on their own as well.
+            nb = w.seqlen // S
+            cols = np.arange(h % w.stride, nb, w.stride)
+            rows = (cols[:, None] * S + np.arange(S)[None, :]).ravel()
+            for n, ref in (("dk", dK), ("dv", dV)):
+                e = G.rel_l2(G.to_f64(out[n][b, h])[rows], ref[rows])
+                print("   %s head (%d,%d) %s stripe columns rel-L2 %.3e" % (n, b, h, which, e), flush=True)
+                assert e <= 2e-2, (which, n, b, h, e)
+
+
+def _both_backwards(w, bits):
+    outs = {"recomputing": G.run_fwd_bwd(w, *bits), "keeping dS": G.run_fwd_bwd(w, *bits, keep_ds=True)}
+    assert outs["keeping dS"]["ws_bytes"] > outs["recomputing"]["ws_bytes"]
+    return outs
 
 
 def test_1p3b_8k_full():
     w = synth.WORKLOADS["1p3b_8k"]
     print("full-size case", w.name, flush=True)
     bits = synth.train_inputs(w)
-    out = G.run_fwd_bwd(w, *bits)
+    outs = _both_backwards(w, bits)
+    out = outs["recomputing"]
     rng = np.random.default_rng(1)
     _check_forward_rows(w, out["o"], out["lse"], bits[:3], [(b, (5 * b + 2 * k) % w.heads) for b in range(w.batch) for k in range(2)], rng)
     for b in range(w.batch):          # every (batch, head) pair: under a second of oracle each
         for h in range(w.heads):
-            _check_backward_head(w, out, bits, b, h, stripe_columns=(h % 5 == 0))
+            _check_backward_head(w, outs, bits, b, h, stripe_columns=(h % 5 == 0))
     # every output finite and nothing left unwritten
-    for n in ("o", "dq", "dk", "dv"):
-        assert torch.isfinite(out[n].float()).all()
+    for out in outs.values():
+        for n in ("o", "dq", "dk", "dv"):
+            assert torch.isfinite(out[n].float()).all()
 
 
 def test_7b_32k_full():
     w = synth.WORKLOADS["7b_32k"]
     print("full-size case", w.name, flush=True)
     bits = synth.train_inputs(w)
-    out = G.run_fwd_bwd(w, *bits)
+    outs = _both_backwards(w, bits)
+    out = outs["recomputing"]
     rng = np.random.default_rng(2)
     _check_forward_rows(w, out["o"], out["lse"], bits[:3], [(0, h) for h in (0, 3, 5, 10, 15, 16, 21, 26, 31)], rng)
     for h in (0, 5, 15, 16, 21, 31):   # both ends of the stripe offsets and between; about ten seconds of oracle each
-        _check_backward_head(w, out, bits, 0, h, stripe_columns=True)
-    for n in ("o", "dq", "dk", "dv"):
-        assert torch.isfinite(out[n].float()).all()
+        _check_backward_head(w, outs, bits, 0, h, stripe_columns=True)
+    for out in outs.values():
+        for n in ("o", "dq", "dk", "dv"):
+            assert torch.isfinite(out[n].float()).all()
 
 
 def test_7b_128k_forward_full():

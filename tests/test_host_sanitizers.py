@@ -1,5 +1,5 @@
 """The host side of the library (the closed-form layout builder, the builder from caller-supplied
-rows and the merged tile lists; integer code, no HIP) compiled with g++ under AddressSanitizer and
+rows, the merged tile lists and the unit table of the backward that keeps dS; integer code, no HIP) compiled with g++ under AddressSanitizer and
 UndefinedBehaviorSanitizer and driven over the training workloads, a random parameter sweep and
 the inputs the builders reject."""
 
@@ -48,6 +48,21 @@ static void exercise(const s2_layout_params& p) {
   CHECK((int)t.ptr.size() == H * t.tiles_per_head + 1 && t.ptr.back() == (int32_t)t.ent.size());
   s2::build_tiles(L, s2::kBwdBN / S > 0 ? s2::kBwdBN / S : 1, true, t);
   CHECK((int)t.members.size() == H * t.tiles_per_head * t.group);
+  // the unit table of the backward that keeps dS (64- and 128-token blocks)
+  if (S >= 64) {
+    s2::build_tiles(L, s2::kBwdBM / S, false, L.q_tiles);
+    s2::build_tiles(L, s2::kBwdBN / S, true, L.kv_tiles);
+    s2::build_ds_units(L);
+    const size_t cpb = (size_t)S / 64;
+    CHECK(L.ds_units == (int64_t)(L.kv_tiles.ent.size() * cpb * 2));
+    CHECK(L.dq_units.size() == L.q_tiles.ent.size() * cpb * 2);
+    int64_t named = 0;
+    for (int32_t u : L.dq_units) {
+      CHECK(u >= -1 && u < L.ds_units);
+      named += u >= 0;
+    }
+    CHECK(named >= L.nnz);  // every kept block has at least one piece with a causal pair
+  }
   // the same pattern handed back as caller-supplied rows
   s2_layout L2;
   CHECK(s2::build_from_csr(H, B, S, L.row_ptr.data(), L.col_idx.data(), L2) == S2_OK);

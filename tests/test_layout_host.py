@@ -414,7 +414,18 @@ def _mask_from_tiles(lay, which, H, Bk):
                     real = [m for m in members if m >= 0]
                     assert real == list(range(real[0], real[0] + len(real)))
             units = [int(e) >> 16 for e in t["ent"][lo:hi]]
-            assert units == sorted(set(units), reverse=cols), "partners strictly ordered, none twice"
+            if cols:
+                # descending, or (an unbroken run of n rows shared by many equal tiles) descending from the
+                # row that is a multiple of n, wrapping round to the run's last row
+                want = sorted(set(units), reverse=True)
+                n = len(units)
+                if units != want:
+                    assert n >= 2 and want[0] - want[-1] == n - 1, "only an unbroken run is rotated"
+                    k = want[0] - (want[0] // n) * n
+                    assert units == want[k:] + want[:k], "rotated to start at a multiple of its length"
+                    assert lens.count(n) + sum(1 for tt in range(tile + 1, T) if int(t["ptr"][h * T + tt + 1]) - int(t["ptr"][h * T + tt]) == n) >= 8
+            else:
+                assert units == sorted(set(units)), "partners strictly ascending, none twice"
             for e in t["ent"][lo:hi]:
                 unit, bits = int(e) >> 16, int(e) & 0xFFFF
                 assert bits != 0 and bits < (1 << (G * sub))
@@ -439,7 +450,8 @@ def test_work_lists_hold_exactly_the_mask(S):
     # the lists the three kernels walk (merged query tiles, merged key tiles) against the oracle's
     # mask, for the rule and for arbitrary patterns, every block size
     rng = np.random.default_rng(40 + S)
-    cases = [orc.block_mask(5, 24, 3, 4), orc.block_mask(3, 10, 1, 0), orc.with_sink(orc.block_mask(2, 18, 2, 7), 1)]
+    cases = [orc.block_mask(5, 24, 3, 4), orc.block_mask(3, 10, 1, 0), orc.with_sink(orc.block_mask(2, 18, 2, 7), 1),
+             orc.block_mask(2, 64, 4, 8)]
     cases += [_random_causal_mask(rng, int(rng.integers(1, 5)), 2 * int(rng.integers(1, 20)), float(rng.random()))
               for _ in range(6)]
     for M in cases:
@@ -455,3 +467,76 @@ def test_work_lists_hold_exactly_the_mask(S):
     v = B.TileView()
     assert B.lib().s2_layout_get_tiles(lay.handle, 3, C.byref(v)) == -2
     assert B.lib().s2_layout_get_tiles(None, 0, C.byref(v)) == -1
+
+
+@pytest.mark.parametrize("S", [64, 128])
+def test_ds_unit_table(S):
+    # the backward that keeps dS: every 64 x 64 piece of a kept block that holds a causal pair has one
+    # unit of its own among the steps of the dK/dV lists, and the dQ lists find exactly those units
+    rng = np.random.default_rng(70 + S)
+    cases = [orc.block_mask(5, 24, 3, 4), orc.block_mask(2, 64, 4, 8), orc.block_mask(3, 11, 1, 0),
+             orc.with_sink(orc.block_mask(2, 18, 2, 7), 1)]
+    cases += [_random_causal_mask(rng, int(rng.integers(1, 5)), int(rng.integers(1, 40)), float(rng.random()))
+              for _ in range(6)]
+    sub = S // 64
+    for M in cases:
+        H, Bk, _ = M.shape
+        row_ptr, col_idx, _, _ = orc.compressed_layout(M)
+        lay = B.s2_layout_from_csr(H, Bk, S, row_ptr, col_idx)
+        kv, dq = B.s2_layout_get_tiles(lay, B.TILES_DKDV), B.s2_layout_get_tiles(lay, B.TILES_DQ)
+        view = B.s2_layout_get_ds_units(lay)
+        assert view["ds_units"] == 2 * sub * len(kv["ent"])
+        assert len(view["dq_units"]) == 2 * sub * len(dq["ent"])
+        # the dK/dV walk, as the header describes it
+        where = {}
+        T, G = kv["tiles_per_head"], kv["group"]
+        assert G == 128 // S and dq["group"] == 128 // S
+        for h in range(H):
+            for t in range(T):
+                mem = kv["members"][(h * T + t) * G:(h * T + t + 1) * G]
+                for e in range(int(kv["ptr"][h * T + t]), int(kv["ptr"][h * T + t + 1])):
+                    ent = int(kv["ent"][e])
+                    for c in range(sub):
+                        q64 = (ent >> 16) * sub + (sub - 1 - c)
+                        for r in range(2):
+                            m = r if sub == 1 else 0
+                            if mem[m] < 0 or not (ent >> m) & 1:
+                                continue
+                            k64 = int(mem[m]) if sub == 1 else int(mem[0]) * 2 + r
+                            if k64 > q64:
+                                continue
+                            assert (h, q64, k64) not in where
+                            where[(h, q64, k64)] = (e * sub + c) * 2 + r
+        assert len(set(where.values())) == len(where) and max(where.values()) < view["ds_units"]
+        # every piece of the mask that holds a causal pair, and nothing else
+        want = {(h, i * sub + a, j * sub + b) for h, i, j in zip(*np.nonzero(M)) for a in range(sub)
+                for b in range(sub) if j * sub + b <= i * sub + a}
+        assert set(where) == want
+        # the dQ walk finds them
+        Tq = dq["tiles_per_head"]
+        for h in range(H):
+            for t in range(Tq):
+                for e in range(int(dq["ptr"][h * Tq + t]), int(dq["ptr"][h * Tq + t + 1])):
+                    ent = int(dq["ent"][e])
+                    for c in range(sub):
+                        k64 = (ent >> 16) * sub + c
+                        for m in range(2):
+                            q64 = 2 * t + m
+                            got = int(view["dq_units"][(e * sub + c) * 2 + m])
+                            kept = q64 // sub < Bk and bool(M[h, q64 // sub, k64 // sub]) and k64 <= q64
+                            assert got == (where[(h, q64, k64)] if kept else -1), (h, t, e, c, m)
+    for S_other in (16, 32):
+        lay = B.s2_layout_build(B.layout_params(2, 16, S_other, 2, 4))
+        view = B.s2_layout_get_ds_units(lay)
+        assert view["ds_units"] == 0 and len(view["dq_units"]) == 0
+    v = B.DsUnitsView()
+    assert B.lib().s2_layout_get_ds_units(None, C.byref(v)) == -1
+    # the workspace that selects the path: the small one plus 8 KiB per unit and batch element, and
+    # only the small one where the path does not apply
+    lay = B.s2_layout_build(B.layout_params(4, 8, S, 2, 3))
+    units = B.s2_layout_get_ds_units(lay)["ds_units"]
+    small = B.s2_attn_bwd_workspace_bytes(3, 4, 8 * S, 128)
+    assert B.s2_attn_bwd_layout_workspace_bytes(lay, 3, 4, 8 * S, 128) == small + 3 * units * 8192
+    assert B.s2_attn_bwd_layout_workspace_bytes(lay, 3, 4, 8 * S, 64) == B.s2_attn_bwd_workspace_bytes(3, 4, 8 * S, 64)
+    assert B.s2_attn_bwd_layout_workspace_bytes(lay, 3, 5, 8 * S, 128) == B.s2_attn_bwd_workspace_bytes(3, 5, 8 * S, 128)
+    assert B.s2_attn_bwd_layout_workspace_bytes(lay, 3, 4, 4 * S, 128) == B.s2_attn_bwd_workspace_bytes(3, 4, 4 * S, 128)
