@@ -68,7 +68,10 @@ __device__ inline RowBlocks row_blocks(const DecodeParams& p, int head, int i) {
   return r;
 }
 
-template <int D, bool PAGED>
+// GATHER: the instantiation for 16-token blocks, where a unit of work is four consecutive kept blocks
+// of the row's list side by side, so that every load still fetches rows the query attends (a 16-token
+// block on its own would fill a quarter of the 64 rows a unit loads).
+template <int D, bool PAGED, bool GATHER>
 __global__ __launch_bounds__(256, 2) void decode_split_kernel(const DecodeParams p) {
   constexpr int LPR = D / 8;     // lanes covering one row
   constexpr int RPI = 64 / LPR;  // rows covered by one wavefront-wide load
@@ -90,9 +93,10 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(const DecodeParams
   const int S = p.block_size;
   const int U = min(S, kChunk);  // tokens per unit of work: 64, or a whole block when it is shorter
   const int cpb = S / U;
+  constexpr int BPU = 4;         // GATHER: blocks per unit
   const int i = (L - 1) / S;
   const RowBlocks rb = row_blocks(p, h, i);
-  const int units = rb.count * cpb;
+  const int units = GATHER ? (rb.count + BPU - 1) / BPU : rb.count * cpb;
   const int u_lo = (int)((int64_t)units * split / p.num_splits);
   const int u_hi = (int)((int64_t)units * (split + 1) / p.num_splits);
 
@@ -114,9 +118,47 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(const DecodeParams
   for (int e = 0; e < 8; ++e) acc[e] = 0.f;
 
   for (int u = u_lo + wave; u < u_hi; u += 4) {
+    bf16x8 kr[NI], vr[NI];
+    bool live[NI];  // GATHER: whether my row of load n is a token the query attends
+    int tok0 = 0, tok_end = 0;
+    if constexpr (GATHER) {
+      // slot RPI * n + g of the unit is token (slot mod 16) of the unit's block (slot div 16); a slot
+      // past the list's end, past L or in a block that is not resident reads the first token of the
+      // row's first kept block instead (it exists) and counts for nothing
+      int64_t dead = (int64_t)rb.block(0) * S * p.kv_st;
+      if (PAGED) {
+        const int page = table[rb.block(0)];
+        dead = (page >= 0 && page < p.num_pages) ? (int64_t)page * p.kv_ss : 0;  // else page 0 of the pool
+      }
+      int64_t row_off[NI];
+#pragma unroll
+      for (int n = 0; n < NI; ++n) {
+        const int slot = RPI * n + g;
+        const int bi = u * BPU + (slot >> 4);
+        const bool inside = bi < rb.count;
+        const int blk = rb.block(inside ? bi : 0);
+        const int tok = blk * S + (slot & 15);
+        bool ok = inside && tok < L;
+        int64_t off = (int64_t)tok * p.kv_st;
+        if (PAGED) {
+          const int page = table[blk];
+          const bool resident = page >= 0 && page < p.num_pages;
+          // the lane that holds a block's first row counts a kept block that is not there
+          if (inside && !resident && (slot & 15) == 0 && lane == 0) ++n_missing;
+          ok = ok && resident;
+          off = (int64_t)page * p.kv_ss + (int64_t)(slot & 15) * p.kv_st;
+        }
+        live[n] = ok;
+        row_off[n] = ok ? off : dead;
+      }
+#pragma unroll
+      for (int n = 0; n < NI; ++n) kr[n] = *reinterpret_cast<const bf16x8*>(kb + row_off[n]);
+#pragma unroll
+      for (int n = 0; n < NI; ++n) vr[n] = *reinterpret_cast<const bf16x8*>(vb + row_off[n]);
+    } else {
     const int blk = rb.block(u / cpb);
-    const int tok0 = blk * S + (u % cpb) * U;
-    const int tok_end = min(L, tok0 + U);  // a 32-token block fills half of the 64 rows loaded
+    tok0 = blk * S + (u % cpb) * U;
+    tok_end = min(L, tok0 + U);  // a 32-token block fills half of the 64 rows loaded
     if (tok0 >= L) continue;  // second half of a partial last block
     // row `tok` of the cache is at base + (tok - shift) * kv_st
     int64_t base = 0;
@@ -130,7 +172,6 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(const DecodeParams
       base = (int64_t)page * p.kv_ss;
       shift = blk * S;
     }
-    bf16x8 kr[NI], vr[NI];
 #pragma unroll
     for (int n = 0; n < NI; ++n) {
       const int tok = min(tok0 + RPI * n + g, tok_end - 1);  // clamp: never read past the unit
@@ -141,6 +182,7 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(const DecodeParams
       const int tok = min(tok0 + RPI * n + g, tok_end - 1);
       vr[n] = *reinterpret_cast<const bf16x8*>(vb + base + (int64_t)(tok - shift) * p.kv_st);
     }
+    }
     float s[NI];
     float mx = kNegInf;
 #pragma unroll
@@ -150,13 +192,14 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(const DecodeParams
       for (int e = 0; e < 8; ++e) d = __builtin_fmaf(qv[e], (float)kr[n][e], d);
 #pragma unroll
       for (int m = 1; m < LPR; m <<= 1) d += __shfl_xor(d, m, 64);
-      if (tok0 + RPI * n + g >= tok_end) d = kNegInf;
+      if (GATHER ? !live[n] : tok0 + RPI * n + g >= tok_end) d = kNegInf;
       s[n] = d;
       mx = fmaxf(mx, d);
     }
 #pragma unroll
     for (int m = LPR; m < 64; m <<= 1) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
     const float m_new = fmaxf(m_run, mx);  // finite: token tok0 < L is always valid
+    if (GATHER && m_new == kNegInf) continue;  // nothing live yet (a paged cache with the unit's blocks missing)
     const float alpha = fast_exp2((m_run - m_new) * cl);
     const float mc = m_new * cl;
     float psum = 0.f;
@@ -234,10 +277,17 @@ __global__ __launch_bounds__(D) void decode_reduce_kernel(const DecodeParams p) 
 template <int D>
 hipError_t launch_one(const DecodeParams& p, hipStream_t stream) {
   const int bh = p.nseq * p.heads;
-  if (p.block_table)
-    hipLaunchKernelGGL((decode_split_kernel<D, true>), dim3(bh * p.num_splits), dim3(256), 0, stream, p);
-  else
-    hipLaunchKernelGGL((decode_split_kernel<D, false>), dim3(bh * p.num_splits), dim3(256), 0, stream, p);
+  const dim3 grid(bh * p.num_splits);
+  if (p.block_size == 16) {
+    if (p.block_table)
+      hipLaunchKernelGGL((decode_split_kernel<D, true, true>), grid, dim3(256), 0, stream, p);
+    else
+      hipLaunchKernelGGL((decode_split_kernel<D, false, true>), grid, dim3(256), 0, stream, p);
+  } else if (p.block_table) {
+    hipLaunchKernelGGL((decode_split_kernel<D, true, false>), grid, dim3(256), 0, stream, p);
+  } else {
+    hipLaunchKernelGGL((decode_split_kernel<D, false, false>), grid, dim3(256), 0, stream, p);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((decode_reduce_kernel<D>), dim3(bh), dim3(D), 0, stream, p);
