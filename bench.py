@@ -588,6 +588,13 @@ def main():
             torch.cuda.empty_cache()
         extra["7b_decode"] = bench_decode(synth.WORKLOADS["7b_decode"], 20, 3)
         extra["7b_decode_paged"] = bench_decode_paged(synth.WORKLOADS["7b_decode"], 20, 3)
+        # the same cache read through 16-token blocks (the finest shards the paper mentions; 64 local
+        # blocks and a stripe every 64 keep the local window's tokens and a quarter of each stripe's),
+        # and one sequence on its own (two launches of a few microseconds: bound by launch latency)
+        import dataclasses
+        dw = synth.WORKLOADS["7b_decode"]
+        extra["7b_decode_16_token_blocks"] = bench_decode(dataclasses.replace(dw, block_size=16, local_blocks=64, stride=64), 20, 3)
+        extra["7b_decode_one_sequence_32k"] = bench_decode(dataclasses.replace(dw, batch=1, min_len=dw.max_len), 50, 5)
         extra["7b_prefill_varlen"] = bench_prefill_varlen(synth.WORKLOADS["7b_32k"], 10, 2)
 
     # last, so that a second of pure MFMA load does not heat the chip under the numbers above
@@ -599,7 +606,7 @@ def main():
                                      "work per MFMA beside it; a pure 2 GiB read; coalesced fp32 atomic adds into a 512 MiB buffer")
         roof["frac_of_measured_mfma"] = roof["achieved"] / ceilings["mfma_bf16_tflops"]
         if extra is not None:
-            for name in ("7b_decode", "7b_decode_paged"):
+            for name in ("7b_decode", "7b_decode_paged", "7b_decode_16_token_blocks", "7b_decode_one_sequence_32k"):
                 extra[name]["frac_of_measured_read"] = extra[name]["hbm_gbs"] / ceilings["hbm_read_gbs"]
     out = {
         "metric": "effective sparse-attn TFLOP/s fwd+bwd (% MFMA peak) + speedup vs dense causal"

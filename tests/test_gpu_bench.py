@@ -36,3 +36,15 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True,
                        text=True, timeout=120, cwd=ROOT)
     assert r.returncode != 0 and "one GPU" in (r.stderr + r.stdout)
+
+
+@pytest.mark.gpu
+def test_bench_times_both_forms_of_the_backward():
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", "1p3b_8k", "--steps", "3",
+                        "--warmup", "1", "--no-extra", "--no-ceilings", "--no-dense", "--no-cpu-baseline"],
+                       capture_output=True, text=True, timeout=600, cwd=ROOT)
+    assert r.returncode == 0, r.stderr[-2000:]
+    d = json.loads(r.stdout.strip().splitlines()[-1])["detail"]
+    rec, keep = d["backward_recomputing"], d["backward_keeping_ds"]
+    assert keep["workspace_bytes"] > rec["workspace_bytes"] and rec["ms"] > 0 and keep["ms"] > 0
+    assert d["backward_path"] == ("keeping dS" if keep["ms"] < rec["ms"] else "recomputing")
