@@ -232,6 +232,10 @@ def bench_train(w, steps, warmup, with_dense=True, with_bwd=True, dense_steps=3,
         dflops = (14.0 if with_bwd else 4.0) * D * dense_pairs
         res["dense_tflops"] = dflops / (res["dense_ms_per_step"] * 1e-3) / 1e12
         res["speedup_vs_dense"] = res["dense_ms_per_step"] / ms_step
+        if with_bwd:
+            # the dense kernels have no form that keeps dS (it would be 2 bytes per causal pair): like for like,
+            # both sides with the recomputing backward
+            res["speedup_vs_dense_both_recomputing"] = res["dense_ms_per_step"] / (res["ms_fwd"] + res["backward_recomputing"]["ms"])
         res["speedup_vs_dense_fwd"] = res["dense_ms_fwd"] / res["ms_fwd"]
         if hybrid_layers:
             # Attention time of a whole layer stack that keeps a few layers dense (section 4.2's
@@ -267,7 +271,9 @@ def bench_train(w, steps, warmup, with_dense=True, with_bwd=True, dense_steps=3,
     dom = max(kernels, key=lambda n: kernels[n][0])
     ach = kernels[dom][1] * D * pairs / (kernels[dom][0] * 1e-3) / 1e12
     res["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
-                       "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": measured_traffic(w.name, dom),
+                       "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
+                       "traffic": measured_traffic(w.name, dom + ("_keeping_ds" if dom == "dkdv_kernel" and with_bwd and
+                                                                  res["backward_path"] == "keeping dS" else "")),
                        "avg_launch_ms": kernels[dom][0],
                        "algorithmic_flops_per_launch": kernels[dom][1] * D * pairs}
     if with_bwd:
@@ -443,7 +449,9 @@ def bench_prefill_varlen(w, steps, warmup, nseq=12, min_len=1024):
                 speedup_vs_padded=ms_pad / ms)
 
 
-def bench_decode(w, steps, warmup):
+def bench_decode(w, steps, warmup, auto_splits=False):
+    """auto_splits: leave the split count to the library (it cuts the public default down where a row has
+    few units of work); the workspace is sized for the public default either way."""
     import torch
     from paper_2407_17678_amd import binding as B
     from paper_2407_17678_amd import synth
@@ -464,7 +472,7 @@ def bench_decode(w, steps, warmup):
     splits = B.s2_attn_decode_default_splits(nseq, H, max_len)
     ws = torch.empty(B.s2_attn_decode_workspace_bytes(nseq, H, D, max_len, splits), dtype=torch.uint8,
                      device="cuda")
-    run = lambda: B.s2_attn_decode(p, q, kc, vc, sl, o, lse, w.scale, ws, max_len, num_splits=splits)
+    run = lambda: B.s2_attn_decode(p, q, kc, vc, sl, o, lse, w.scale, ws, max_len, num_splits=0 if auto_splits else splits)
     prewarm(run)
     ms = time_events(run, steps, warmup)
     # algorithmic bytes: K and V rows of the kept tokens, plus q, o and the split partials
@@ -481,7 +489,8 @@ def bench_decode(w, steps, warmup):
     other = nseq * H * D * 2 * 2 + 2 * nseq * H * splits * (D + 2) * 4
     dense_bytes = int(lens.astype(np.int64).sum()) * H * D * 2 * 2
     gbs = (kv_bytes + other) / (ms * 1e-3) / 1e9
-    return dict(workload=w.name, nseq=nseq, heads=H, head_dim=D, max_len=max_len, splits=int(splits),
+    return dict(workload=w.name, nseq=nseq, heads=H, head_dim=D, max_len=max_len, block_size=w.block_size,
+                splits="left to the library" if auto_splits else int(splits),
                 mean_len=float(lens.mean()), ms=ms, kept_tokens=int(tokens), algorithmic_gb=(kv_bytes + other) / 1e9,
                 dense_gb=dense_bytes / 1e9, hbm_gbs=gbs, frac_hbm_peak=gbs / PEAK_HBM_GBS)
 
@@ -594,7 +603,7 @@ def main():
         import dataclasses
         dw = synth.WORKLOADS["7b_decode"]
         extra["7b_decode_16_token_blocks"] = bench_decode(dataclasses.replace(dw, block_size=16, local_blocks=64, stride=64), 20, 3)
-        extra["7b_decode_one_sequence_32k"] = bench_decode(dataclasses.replace(dw, batch=1, min_len=dw.max_len), 50, 5)
+        extra["7b_decode_one_sequence_32k"] = bench_decode(dataclasses.replace(dw, batch=1, min_len=dw.max_len), 50, 5, auto_splits=True)
         extra["7b_prefill_varlen"] = bench_prefill_varlen(synth.WORKLOADS["7b_32k"], 10, 2)
 
     # last, so that a second of pure MFMA load does not heat the chip under the numbers above

@@ -49,9 +49,12 @@ def _per_kernel(path, counter):
             if r["Counter_Name"] != counter:
                 continue
             name, val = r["Kernel_Name"], float(r["Counter_Value"])
-            m = re.search(r"s2::.*?(\w+_kernel)<", name)
+            m = re.search(r"s2::.*?(\w+_kernel)<([^>]*)>", name)
             if m:
-                sums[m.group(1)].append(val)
+                # the dK/dV instantiation that also leaves dS in the workspace (last template argument) is a
+                # kernel of its own as far as traffic goes
+                keeps = m.group(1) == "dkdv_kernel" and m.group(2).replace(" ", "").endswith(",true")
+                sums[m.group(1) + ("_keeping_ds" if keeps else "")].append(val)
             elif "copyBuffer" in name:   # the runtime's device-to-device copy kernel
                 copies.append(val)
     # the calibration copy (1 GiB) is the largest device-to-device copy of the run
