@@ -35,3 +35,14 @@ def test_fingerprint_follows_the_kernel_sources():
         if name.startswith("traffic_") and name.endswith(".txt"):
             with open(os.path.join(prof, name)) as fh:
                 assert fh.readline().startswith("# sources "), name
+
+
+def test_the_ds_keeping_dkdv_instantiation_is_told_apart(tmp_path):
+    plain = "void s2::(anonymous namespace)::dkdv_kernel<128, false, 64, false, false>(s2::AttnParams)"
+    keeps = "void s2::(anonymous namespace)::dkdv_kernel<128, false, 64, false, true>(s2::AttnParams)"
+    f, w = tmp_path / "f.csv", tmp_path / "w.csv"
+    copy = "__amd_rocclr_copyBuffer"
+    f.write_text(HEAD + _row(copy, "FETCH_SIZE", 524288) + _row(plain, "FETCH_SIZE", 1000) + _row(keeps, "FETCH_SIZE", 2000))
+    w.write_text(HEAD + _row(copy, "WRITE_SIZE", 1048576) + _row(plain, "WRITE_SIZE", 10) + _row(keeps, "WRITE_SIZE", 4000))
+    rows = {l.split()[0]: int(l.split()[1]) for l in P.traffic("7b_32k", str(f), str(w)).splitlines() if not l.startswith("#")}
+    assert rows == {"dkdv_kernel": (2000 + 10) * 1024, "dkdv_kernel_keeping_ds": (4000 + 4000) * 1024}
