@@ -103,7 +103,9 @@ def test_strided_tensors_backward():
         assert G.rel_l2(G.to_f64(got), ref) <= GRAD_TOL, n
 
 
-def test_one_layout_on_two_streams_at_once():
+@pytest.mark.parametrize("keep_ds", [False, True])
+def test_one_layout_on_two_streams_at_once(keep_ds):
+    # (both forms of the backward: with the small workspace, and with the one that holds dS)
     # a layout handle is immutable: forward + backward of two different batches, issued on two
     # streams without waiting for each other, must equal the same calls made one after the other
     # (each call has its own tensors and workspace; nothing in the library is shared between calls)
@@ -117,7 +119,8 @@ def test_one_layout_on_two_streams_at_once():
         q, k, v, g = (torch.randn((2, H, N, D), device="cuda", generator=gen).to(torch.bfloat16) for _ in range(4))
         bufs = dict(o=torch.empty_like(q), lse=torch.empty((2, H, N), dtype=torch.float32, device="cuda"),
                     dq=torch.empty_like(q), dk=torch.empty_like(q), dv=torch.empty_like(q),
-                    ws=torch.empty(B.s2_attn_bwd_workspace_bytes(2, H, N, D), dtype=torch.uint8, device="cuda"))
+                    ws=torch.empty(B.s2_attn_bwd_layout_workspace_bytes(lay, 2, H, N, D) if keep_ds else
+                                   B.s2_attn_bwd_workspace_bytes(2, H, N, D), dtype=torch.uint8, device="cuda"))
         sets.append((q, k, v, g, bufs))
 
     def run(i, stream):
@@ -173,5 +176,13 @@ def test_peaked_softmax_and_wide_dynamic_range():
     # LSE values of 20-60 in fp32 carry an ulp of 4e-6; the stated bound still holds
     assert np.abs(G.to_f64(lse) - LSE).max() <= 1e-3
     for n, got, ref in (("dq", dq, dQ), ("dk", dk, dK), ("dv", dv, dV)):
+        assert torch.isfinite(got.float()).all()
+        assert G.rel_l2(G.to_f64(got), ref) <= GRAD_TOL, n
+    # the same through the backward that keeps dS (its dQ takes the bf16-rounded dS)
+    ws2 = torch.full((B.s2_attn_bwd_layout_workspace_bytes(lay, 1, H, N, D),), 0xFF, dtype=torch.uint8, device="cuda")
+    dq2, dk2, dv2 = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+    B.s2_attn_bwd(lay, q, k, v, o, lse, g, dq2, dk2, dv2, w.scale, ws2)
+    torch.cuda.synchronize()
+    for n, got, ref in (("dq", dq2, dQ), ("dk", dk2, dK), ("dv", dv2, dV)):
         assert torch.isfinite(got.float()).all()
         assert G.rel_l2(G.to_f64(got), ref) <= GRAD_TOL, n

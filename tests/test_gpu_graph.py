@@ -57,7 +57,9 @@ def test_decode_step_in_a_graph():
     assert torch.equal(o, want_o) and torch.equal(lse, want_lse)
 
 
-def test_forward_backward_in_a_graph():
+@pytest.mark.parametrize("keep_ds", [False, True])
+def test_forward_backward_in_a_graph(keep_ds):
+    """Both forms of the backward: the small workspace, and the one that holds dS between the launches."""
     w = synth.WORKLOADS["1p3b_8k"]
     Bt, H, N, D, S = 1, 4, 2048, w.head_dim, w.block_size
     lay = B.s2_layout_build(B.layout_params(H, N // S, S, w.local_blocks, w.stride))
@@ -65,7 +67,9 @@ def test_forward_backward_in_a_graph():
     o = torch.empty_like(q)
     lse = torch.empty((Bt, H, N), dtype=torch.float32, device="cuda")
     dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
-    ws = torch.empty(B.s2_attn_bwd_workspace_bytes(Bt, H, N, D), dtype=torch.uint8, device="cuda")
+    nbytes = B.s2_attn_bwd_layout_workspace_bytes(lay, Bt, H, N, D) if keep_ds else B.s2_attn_bwd_workspace_bytes(Bt, H, N, D)
+    assert not keep_ds or nbytes > B.s2_attn_bwd_workspace_bytes(Bt, H, N, D)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
 
     def step():
         B.s2_attn_fwd(lay, q, k, v, o, lse, w.scale)
