@@ -388,7 +388,8 @@ def bench_decode_paged(w, steps, warmup):
             assert resident[b][h][-1] == i
     kv_bytes = tokens * D * 2 * 2
     # q, o, split partials, and the table entries looked up
-    other = nseq * H * D * 2 * 2 + 2 * nseq * H * splits * (D + 2) * 4 + sum(len(r) for row in resident for r in row) * 4
+    partials = 0 if splits == 1 else 2 * nseq * H * splits * (D + 2) * 4   # one split writes the result itself
+    other = nseq * H * D * 2 * 2 + partials + sum(len(r) for row in resident for r in row) * 4
     gbs = (kv_bytes + other) / (ms * 1e-3) / 1e9
     contiguous_gb = 2 * nseq * H * max_len * D * 2 / 1e9
     return dict(workload=w.name + "_paged", nseq=nseq, heads=H, head_dim=D, max_len=max_len, splits=int(splits),
@@ -486,7 +487,8 @@ def bench_decode(w, steps, warmup, auto_splits=False):
             n_str = (local_lo - 1 - o_h) // w.stride + 1 if o_h < local_lo else 0
             tokens += n_str * S + (L - local_lo * S)
     kv_bytes = tokens * D * 2 * 2
-    other = nseq * H * D * 2 * 2 + 2 * nseq * H * splits * (D + 2) * 4
+    partials = 0 if splits == 1 and not auto_splits else 2 * nseq * H * splits * (D + 2) * 4   # one split writes the result itself
+    other = nseq * H * D * 2 * 2 + partials
     dense_bytes = int(lens.astype(np.int64).sum()) * H * D * 2 * 2
     gbs = (kv_bytes + other) / (ms * 1e-3) / 1e9
     return dict(workload=w.name, nseq=nseq, heads=H, head_dim=D, max_len=max_len, block_size=w.block_size,

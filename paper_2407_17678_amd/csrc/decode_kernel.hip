@@ -12,7 +12,8 @@
 //
 // Split-KV: the list of 64-token units of one (sequence, head) is cut into num_splits pieces, one
 // workgroup each; the four wavefronts of a workgroup take units round-robin and merge their
-// (max, sum, accumulator) through LDS; a second kernel merges the splits.
+// (max, sum, accumulator) through LDS; a second kernel merges the splits.  With one split per
+// (sequence, head) the first kernel writes the result itself and the second is not launched.
 #include <hip/hip_runtime.h>
 
 #include "config.h"
@@ -245,6 +246,14 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(const DecodeParams
         a += sh_acc[w][tid] * wgt;
       }
     }
+    if (p.num_splits == 1) {
+      // the only split of its (sequence, head): the result itself, no partials and no second kernel
+      // (l == 0 only when nothing was attended: a paged cache with every kept block missing)
+      const __bf16 out = (__bf16)(l > 0.f ? a / l : 0.f);
+      p.o[(int64_t)bh * D + tid] = *reinterpret_cast<const uint16_t*>(&out);
+      if (tid == 0 && p.lse) p.lse[bh] = l > 0.f ? m * p.scale + __logf(l) : kNegInf;
+      return;
+    }
     p.part_acc[(int64_t)item * D + tid] = a;
     if (tid == 0) {
       p.part_ml[(int64_t)item * 2 + 0] = m;
@@ -289,7 +298,7 @@ hipError_t launch_one(const DecodeParams& p, hipStream_t stream) {
     hipLaunchKernelGGL((decode_split_kernel<D, false, false>), grid, dim3(256), 0, stream, p);
   }
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  if (e != hipSuccess || p.num_splits == 1) return e;  // a single split writes the result itself
   hipLaunchKernelGGL((decode_reduce_kernel<D>), dim3(bh), dim3(D), 0, stream, p);
   return hipGetLastError();
 }
