@@ -154,3 +154,51 @@ def test_smaller_workspace_takes_the_other_path_and_one_byte_short_too():
         assert torch.equal(a, b), "one byte short of the larger size: the recomputing path, bit for bit"
     for a, b in zip(res[0], res[2]):
         assert G.rel_l2(G.to_f64(b), G.to_f64(a)) <= 5e-3
+
+
+def _sweep_cases(n, seed=20240719):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        S = int(rng.choice([64, 128]))
+        H = int(rng.integers(1, 10))
+        batch = int(rng.integers(1, 4))
+        Bk = int(rng.integers(1, 13 if S == 64 else 9)) * (2 if S == 64 else 1)   # whole 128-row tiles
+        B_l = int(rng.integers(1, min(Bk, 6) + 2))          # may exceed the number of blocks
+        stride = int(rng.choice([0, 1, 2, 3, 5, 8, 11]))
+        base = int(rng.integers(0, 9))
+        window = int(rng.choice([0, 0, 0, 4, 9]))
+        out.append((S, H, batch, Bk, B_l, stride, base, window))
+    return out
+
+
+@pytest.mark.parametrize("case", _sweep_cases(20), ids=lambda c: "S%d_H%d_b%d_B%d_L%d_V%d_o%d_w%d" % c)
+def test_random_case(case):
+    """A seeded sweep over block size, heads, batch, length, window, stride, head index base and stripe
+    window, each through the backward that keeps dS, against the fp64 oracle."""
+    S, H, batch, Bk, B_l, stride, base, window = case
+    N, D = Bk * S, 128
+    w = dataclasses.replace(synth.WORKLOADS["1p3b_8k"], block_size=S, local_blocks=B_l, stride=stride,
+                            window_blocks=window)
+    print("keep-dS sweep case", case, flush=True)
+    qb, kb, vb, gb = synth.train_inputs(w, heads=H, batch=batch, seqlen=N)
+    lay = B.s2_layout_build(B.layout_params(H, Bk, S, B_l, stride, base, window, 0))
+    M = orc.block_mask(H, Bk, B_l, stride, base, window)
+    q, k, v, g = G.to_dev(qb), G.to_dev(kb), G.to_dev(vb), G.to_dev(gb)
+    o = torch.empty_like(q)
+    lse = torch.empty((batch, H, N), dtype=torch.float32, device="cuda")
+    dq, dk, dv = (torch.full_like(q, float("nan")) for _ in range(3))
+    nbytes = B.s2_attn_bwd_layout_workspace_bytes(lay, batch, H, N, D)
+    assert nbytes > B.s2_attn_bwd_workspace_bytes(batch, H, N, D)
+    ws = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device="cuda")
+    B.s2_attn_fwd(lay, q, k, v, o, lse, w.scale)
+    B.s2_attn_bwd(lay, q, k, v, o, lse, g, dq, dk, dv, w.scale, ws)
+    torch.cuda.synchronize()
+    dQ, dK, dV, O, LSE = orc.attention_backward(G.bits_f64(qb), G.bits_f64(kb), G.bits_f64(vb), G.bits_f64(gb),
+                                                M, S, w.scale)
+    for n, got_t, ref in (("dq", dq, dQ), ("dk", dk, dK), ("dv", dv, dV)):
+        got = G.to_f64(got_t)
+        assert np.isfinite(got).all(), n
+        for b in range(batch):
+            for h in range(H):
+                assert G.rel_l2(got[b, h], ref[b, h]) <= GRAD_TOL, (n, b, h)
