@@ -288,6 +288,8 @@ __device__ __forceinline__ void wait_all_loads() {
 template <int N>
 __device__ __forceinline__ void wait_loads_but() {
   static_assert(N >= 0 && N < 64, "the counter has six bits");
+  // (the caller counts on its last N operations having been issued by now: no store may sink below)
+  asm volatile("" ::: "memory");
   // vmcnt in bits 3:0 and 15:14; expcnt (bits 6:4) and lgkmcnt (bits 11:8) at their maxima: no wait
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
   asm volatile("" ::: "memory");
