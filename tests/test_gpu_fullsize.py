@@ -102,6 +102,39 @@ def test_7b_32k_full():
             assert torch.isfinite(out[n].float()).all()
 
 
+def test_7b_32k_backward_repeats_bitwise_at_full_size():
+    """Both forms of the backward, ten launches each on the full 7b_32k tensors with the workspace
+    scribbled over in between: every launch must reproduce the first bit for bit (the kernels leave
+    stores in flight across their waits for the next chunk and read dS back through a second launch; an
+    ordering mistake there would show as results that differ from run to run)."""
+    w = synth.WORKLOADS["7b_32k"]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(77)
+    shape = (w.batch, w.heads, w.seqlen, w.head_dim)
+    q, k, v, g = (torch.randn(shape, device="cuda", generator=gen).to(torch.bfloat16) for _ in range(4))
+    o = torch.empty_like(q)
+    lse = torch.empty(shape[:3], dtype=torch.float32, device="cuda")
+    lay = B.s2_layout_build(B.layout_params(w.heads, w.seqlen // w.block_size, w.block_size, w.local_blocks, w.stride))
+    B.s2_attn_fwd(lay, q, k, v, o, lse, w.scale)
+    sizes = (B.s2_attn_bwd_workspace_bytes(*shape), B.s2_attn_bwd_layout_workspace_bytes(lay, *shape))
+    assert sizes[1] > sizes[0]
+    for nbytes in sizes:
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        first = None
+        for rep in range(10):
+            ws.random_(0, 255)
+            outs = [torch.full_like(q, float("nan")) for _ in range(3)]
+            B.s2_attn_bwd(lay, q, k, v, o, lse, g, outs[0], outs[1], outs[2], w.scale, ws)
+            torch.cuda.synchronize()
+            if first is None:
+                first = outs
+                assert all(torch.isfinite(t.float()).all() for t in first)
+            else:
+                for a, b_ in zip(first, outs):
+                    assert torch.equal(a, b_), (nbytes, rep)
+        del ws
+
+
 def test_7b_128k_forward_full():
     w = synth.WORKLOADS["7b_128k"]
     print("full-size case", w.name, flush=True)
