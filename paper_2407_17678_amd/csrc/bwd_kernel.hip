@@ -83,7 +83,8 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63, l32 = lane & 31, half = lane >> 5;
   const int T = p.q_tiles.tiles_per_head;
-  const int T_run = VARLEN ? (p.q_rows + kBwdBM - 1) / kBwdBM : T;
+  // (of a packed batch's sequences possibly the last tile only)
+  const int T_run = VARLEN ? (p.varlen_tail ? 1 : (p.q_rows + kBwdBM - 1) / kBwdBM) : T;
   int bh, rank;
   if (!map_workgroup(blockIdx.x, p.batch * p.heads, T_run, bh, rank)) return;
   const int b = bh / p.heads, h = bh - b * p.heads;
@@ -96,6 +97,7 @@ __global__ __launch_bounds__(kThreads, 2) void dq_kernel(const AttnParams p) {
     const int T_seq = (N + kBwdBM - 1) / kBwdBM;
     if (rank >= T_seq) return;
     tile = T_seq - 1 - rank;
+    if (p.varlen_tail && N % kBwdBM == 0) return;  // no partial tile: the fast-path launch has computed them all
   }
   const int S = DENSE ? kChunk : p.block_size;
   // 16-token blocks: a list entry is a unit of two blocks (32 keys, one step) and my 32 query rows
@@ -674,7 +676,17 @@ hipError_t launch_one(const AttnParams& p, int stages, hipStream_t stream) {
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  if ((stages & kBwdDq) && !VARLEN && CH == 64 && dq_pipe_applies(p, DENSE)) {
+  if ((stages & kBwdDq) && VARLEN && CH == 64 && dq_pipe_applies(p, DENSE)) {
+    // packed batch: whole 128-row tiles by the fast path, each sequence's partial last tile by dq_kernel
+    e = launch_dq_pipe(p, DENSE, stream);
+    if (e != hipSuccess) return e;
+    AttnParams tail = p;
+    tail.varlen_tail = 1;
+    hipLaunchKernelGGL((dq_kernel<D, DENSE, CH, VARLEN>), dim3(grid_for(bh, 1)), dim3(kThreads), sizeof(DqSmem<D, CH>),
+                       stream, tail);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  } else if ((stages & kBwdDq) && !VARLEN && CH == 64 && dq_pipe_applies(p, DENSE)) {
     e = launch_dq_pipe(p, DENSE, stream);
     if (e != hipSuccess) return e;
   } else if (stages & kBwdDq) {

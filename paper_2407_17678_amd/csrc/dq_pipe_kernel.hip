@@ -35,7 +35,10 @@ struct DqPipeSmem {
   uint16_t v[2][DmaTile<D, 64, 4>::kElems];
 };
 
-template <int D, bool DENSE>
+// VARLEN: a packed batch of sequences of different lengths.  A workgroup finds its sequence's rows in
+// cu_seqlens and treats them as a sequence of its own; this kernel computes the whole 128-row tiles of
+// each sequence (all their keys exist), a partial last tile is left to dq_kernel.
+template <int D, bool DENSE, bool VARLEN = false>
 __global__ __launch_bounds__(kThreads, 2) void dq_pipe_kernel(const AttnParams p) {
   typedef DmaTile<D, 64, 4> Tile;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -53,18 +56,27 @@ __global__ __launch_bounds__(kThreads, 2) void dq_pipe_kernel(const AttnParams p
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63, l32 = lane & 31, half = lane >> 5;
   const int T = p.q_tiles.tiles_per_head;
+  const int T_run = VARLEN ? p.q_rows / BM : T;  // packed batch: whole tiles of the longest length allowed
   int bh, rank;
-  if (!map_workgroup(blockIdx.x, p.batch * p.heads, T, bh, rank)) return;
+  if (!map_workgroup(blockIdx.x, p.batch * p.heads, T_run, bh, rank)) return;
   const int b = bh / p.heads, h = bh - b * p.heads;
-  const int tile = DENSE ? (T - 1 - rank) : p.q_tiles.order[h * T + rank];
-  const int N = p.seqlen;
+  int tile = DENSE ? (T - 1 - rank) : VARLEN ? 0 : p.q_tiles.order[h * T + rank];
+  int N = p.seqlen, row_base = 0;  // my sequence's length, and the rows of the tensors before it
+  if (VARLEN) {
+    const int lo = p.cu_seqlens[b], hi = p.cu_seqlens[b + 1];
+    row_base = min(max(lo, 0), p.seqlen);  // whatever the array holds, stay inside the tensors
+    N = min(min(max(hi - lo, 0), p.q_rows), p.seqlen - row_base);
+    const int T_full = N / BM;
+    if (rank >= T_full) return;
+    tile = T_full - 1 - rank;
+  }
   const int S = DENSE ? CH : p.block_size;  // 64 or 128
   const int cpb_sh = S == 128 ? 1 : 0, cpb_m = (1 << cpb_sh) - 1;
   const int qw0 = tile * BM + wave * MW;  // first query row of this wavefront
   const int my_member = (qw0 / S) - tile * (BM / S);
 
-  const int64_t q_off = b * p.q_sb + h * p.q_sh;
-  const int64_t kv_off = b * p.kv_sb + h * p.kv_sh;
+  const int64_t q_off = (VARLEN ? row_base * p.q_st : b * p.q_sb) + h * p.q_sh;
+  const int64_t kv_off = (VARLEN ? row_base * p.kv_st : b * p.kv_sb) + h * p.kv_sh;
   // minus the bias the grouped direct loads put into their lane offsets
   const uint16_t* kb = p.k + kv_off - Tile::kBias / 2;
   const uint16_t* vb = p.v + kv_off - Tile::kBias / 2;
@@ -127,7 +139,8 @@ __global__ __launch_bounds__(kThreads, 2) void dq_pipe_kernel(const AttnParams p
     for (int e = 0; e < 8; ++e) part = __builtin_fmaf((float)gf[kk][e], (float)of[e], part);
   }
   const float delta_l = sum_halves(part);
-  const int64_t stat_row = ((int64_t)b * p.heads + h) * N + my_row;
+  const int64_t stat_row = VARLEN ? (int64_t)h * p.seqlen + row_base + my_row  // [heads, rows of the tensors]
+                                  : ((int64_t)b * p.heads + h) * N + my_row;
   const float lse_l = p.lse[stat_row] * kLog2e;
   if (half == 0) {
     p.delta[stat_row] = delta_l;
@@ -310,22 +323,23 @@ __global__ __launch_bounds__(kThreads, 2) void dq_pipe_kernel(const AttnParams p
 
 // A kernel's dynamic LDS limit is a per-device attribute: remember, per device, that it is set.
 constexpr int kMaxDevices = 64;
-std::atomic<unsigned char> g_smem_set[2][kMaxDevices];
+std::atomic<unsigned char> g_smem_set[3][kMaxDevices];
 
-template <bool DENSE>
+template <bool DENSE, bool VARLEN>
 hipError_t launch_one(const AttnParams& p, hipStream_t stream) {
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
   const bool tracked = dev >= 0 && dev < kMaxDevices;
-  if (!tracked || !g_smem_set[DENSE][dev].load(std::memory_order_acquire)) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dq_pipe_kernel<128, DENSE>),
+  constexpr int which = VARLEN ? 2 : DENSE;
+  if (!tracked || !g_smem_set[which][dev].load(std::memory_order_acquire)) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dq_pipe_kernel<128, DENSE, VARLEN>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(DqPipeSmem<128>));
     if (e != hipSuccess) return e;
-    if (tracked) g_smem_set[DENSE][dev].store(1, std::memory_order_release);
+    if (tracked) g_smem_set[which][dev].store(1, std::memory_order_release);
   }
-  const int grid = grid_for(p.batch * p.heads, p.q_tiles.tiles_per_head);
-  hipLaunchKernelGGL((dq_pipe_kernel<128, DENSE>), dim3(grid), dim3(kThreads), sizeof(DqPipeSmem<128>), stream, p);
+  const int grid = grid_for(p.batch * p.heads, VARLEN ? p.q_rows / kBwdBM : p.q_tiles.tiles_per_head);
+  hipLaunchKernelGGL((dq_pipe_kernel<128, DENSE, VARLEN>), dim3(grid), dim3(kThreads), sizeof(DqPipeSmem<128>), stream, p);
   return hipGetLastError();
 }
 
@@ -333,11 +347,14 @@ hipError_t launch_one(const AttnParams& p, hipStream_t stream) {
 
 bool dq_pipe_applies(const AttnParams& p, bool dense) {
   // whole 128-row tiles only: every wavefront of a workgroup owns 32 existing query rows
-  return p.head_dim == 128 && !p.cu_seqlens && (dense || p.block_size >= 64) && p.seqlen % kBwdBM == 0;
+  if (p.cu_seqlens)  // packed batch: the whole tiles of each sequence
+    return !dense && p.head_dim == 128 && p.block_size >= 64 && p.q_rows >= kBwdBM;
+  return p.head_dim == 128 && (dense || p.block_size >= 64) && p.seqlen % kBwdBM == 0;
 }
 
 hipError_t launch_dq_pipe(const AttnParams& p, bool dense, hipStream_t stream) {
-  return dense ? launch_one<true>(p, stream) : launch_one<false>(p, stream);
+  if (p.cu_seqlens) return launch_one<false, true>(p, stream);
+  return dense ? launch_one<true, false>(p, stream) : launch_one<false, false>(p, stream);
 }
 
 }  // namespace s2

@@ -32,7 +32,9 @@ constexpr float kNegInf = -__builtin_inff();
 // VARLEN: a packed batch of sequences of different lengths.  A workgroup finds its sequence's rows
 // in cu_seqlens and treats them as a sequence of its own; the ragged end costs a clamped load plan
 // for the chunks that reach past the last token (their keys are after every query, so the causal
-// mask already drops them) and a per-lane guard on the stores.
+// mask already drops them) and a per-lane guard on the stores.  Where the fast-path kernel applies
+// (fwd_pipe_kernel.hip) it computes each sequence's whole 128-row tiles and this kernel is launched for
+// the partial last tiles only (AttnParams::varlen_tail).
 template <int D, bool DENSE, int CH, bool VARLEN = false>
 __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const AttnParams p) {
   typedef DmaTile<D, CH> Tile;
@@ -47,7 +49,8 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63, l32 = lane & 31, half = lane >> 5;
   const int T = p.fwd_tiles.tiles_per_head;      // tiles of the whole sequence (indexes the lists)
-  const int T_run = (p.q_rows + BM - 1) / BM;    // tiles this launch computes
+  // tiles this launch computes (of a packed batch's sequences possibly the last one only)
+  const int T_run = (VARLEN && p.varlen_tail) ? 1 : (p.q_rows + BM - 1) / BM;
   int bh, rank;
   if (!map_workgroup(blockIdx.x, p.batch * p.heads, T_run, bh, rank)) return;
   const int b = bh / p.heads, h = bh - b * p.heads;
@@ -64,6 +67,7 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
     const int T_seq = (N + BM - 1) / BM;
     if (rank >= T_seq) return;
     tile = T_seq - 1 - rank;
+    if (p.varlen_tail && N % BM == 0) return;  // no partial tile: the fast-path launch has computed them all
   }
   const int S = DENSE ? kChunk : p.block_size;
   // 16-token blocks: a list entry is a unit of two blocks (32 keys, one step) and my 32 query rows
@@ -291,7 +295,7 @@ __global__ __launch_bounds__(kThreads, (CH == 32 ? 3 : 2)) void fwd_kernel(const
 
 template <int D, bool DENSE>
 hipError_t launch_one(const AttnParams& p, hipStream_t stream) {
-  const int grid = grid_for(p.batch * p.heads, (p.q_rows + kFwdBM - 1) / kFwdBM);
+  const int grid = grid_for(p.batch * p.heads, p.varlen_tail ? 1 : (p.q_rows + kFwdBM - 1) / kFwdBM);
   if (!DENSE && p.cu_seqlens) {  // packed variable-length batch (sparse layouts only)
     if (p.block_size <= 32)
       hipLaunchKernelGGL((fwd_kernel<D, false, 32, true>), dim3(grid), dim3(kThreads), 0, stream, p);
@@ -309,6 +313,14 @@ hipError_t launch_one(const AttnParams& p, hipStream_t stream) {
 }  // namespace
 
 hipError_t launch_fwd(const AttnParams& p, bool dense, hipStream_t stream) {
+  if (p.cu_seqlens && fwd_pipe_applies(p, dense)) {
+    // packed batch: whole 128-row tiles by the fast path, each sequence's partial last tile here
+    hipError_t e = launch_fwd_pipe(p, dense, stream);
+    if (e != hipSuccess) return e;
+    AttnParams tail = p;
+    tail.varlen_tail = 1;
+    return launch_one<128, false>(tail, stream);
+  }
   if (fwd_pipe_applies(p, dense)) return launch_fwd_pipe(p, dense, stream);
   if (p.head_dim == 128) return dense ? launch_one<128, true>(p, stream) : launch_one<128, false>(p, stream);
   return dense ? launch_one<64, true>(p, stream) : launch_one<64, false>(p, stream);

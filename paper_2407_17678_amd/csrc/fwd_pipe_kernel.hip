@@ -29,7 +29,10 @@ namespace {
 constexpr float kNegInf = -__builtin_inff();
 constexpr float kTau = 8.0f;  // log2 units a score may exceed the reference maximum by
 
-template <int D, bool DENSE>
+// VARLEN: a packed batch of sequences of different lengths.  A workgroup finds its sequence's rows in
+// cu_seqlens and treats them as a sequence of its own; this kernel computes the whole 128-row tiles of
+// each sequence (all their keys exist), a partial last tile is left to fwd_kernel.
+template <int D, bool DENSE, bool VARLEN = false>
 __global__ __launch_bounds__(kThreads, 2) void fwd_pipe_kernel(const AttnParams p) {
   typedef DmaTile<D, 64, 4> Tile;
   __shared__ __attribute__((aligned(16))) uint16_t sk[2][Tile::kElems];
@@ -51,17 +54,25 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_pipe_kernel(const AttnParams 
   int bh, rank;
   if (!map_workgroup(blockIdx.x, p.batch * p.heads, T_run, bh, rank)) return;
   const int b = bh / p.heads, h = bh - b * p.heads;
-  const bool whole = p.q_row0 == 0 && T_run == T;
-  const int tile = (DENSE || !whole) ? p.q_row0 / BM + (T_run - 1 - rank) : p.fwd_tiles.order[h * T + rank];
-  const int N = p.seqlen;
+  const bool whole = !VARLEN && p.q_row0 == 0 && T_run == T;
+  int tile = (DENSE || !whole) ? p.q_row0 / BM + (T_run - 1 - rank) : p.fwd_tiles.order[h * T + rank];
+  int N = p.seqlen, row_base = 0;  // my sequence's length, and the rows of the tensors before it
+  if (VARLEN) {
+    const int lo = p.cu_seqlens[b], hi = p.cu_seqlens[b + 1];
+    row_base = min(max(lo, 0), p.seqlen);  // whatever the array holds, stay inside the tensors
+    N = min(min(max(hi - lo, 0), p.q_rows), p.seqlen - row_base);
+    const int T_full = N / BM;
+    if (rank >= T_full) return;
+    tile = T_full - 1 - rank;
+  }
   const int S = DENSE ? CH : p.block_size;  // 64 or 128
   const int cpb_sh = S == 128 ? 1 : 0, cpb_m = (1 << cpb_sh) - 1;
   const int qw0 = tile * BM + wave * MW;    // first query row of this wavefront (sequence position)
   const int ql0 = qw0 - p.q_row0;           // the same as a row of q / o / lse
   const int my_member = (qw0 / S) - tile * (BM / S);
 
-  const int64_t q_off = b * p.q_sb + h * p.q_sh;
-  const int64_t kv_off = b * p.kv_sb + h * p.kv_sh;
+  const int64_t q_off = (VARLEN ? row_base * p.q_st : b * p.q_sb) + h * p.q_sh;
+  const int64_t kv_off = (VARLEN ? row_base * p.kv_st : b * p.kv_sb) + h * p.kv_sh;
   // minus the bias the grouped direct loads put into their lane offsets
   const uint16_t* kb = p.k + kv_off - Tile::kBias / 2;
   const uint16_t* vb = p.v + kv_off - Tile::kBias / 2;
@@ -346,19 +357,24 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_pipe_kernel(const AttnParams 
     const u32x4 x = *reinterpret_cast<const u32x4*>(stage + r * RS + 8 * piece);
     *reinterpret_cast<u32x4*>(obase + (int64_t)r * p.q_st + 8 * piece) = x;
   }
-  if (half == 0) p.lse[((int64_t)b * p.heads + h) * p.q_rows + ql0 + l32] = m_ref * p.scale + __logf(l_tot);
+  const int64_t lse_row = VARLEN ? (int64_t)h * p.seqlen + row_base + ql0 + l32  // [heads, rows of the tensors]
+                                 : ((int64_t)b * p.heads + h) * p.q_rows + ql0 + l32;
+  if (half == 0) p.lse[lse_row] = m_ref * p.scale + __logf(l_tot);
 }
 
 }  // namespace
 
 bool fwd_pipe_applies(const AttnParams& p, bool dense) {
-  return p.head_dim == 128 && !p.cu_seqlens && (dense || p.block_size >= 64) && p.q_rows % 128 == 0 &&
-         p.q_row0 % 128 == 0;
+  if (p.cu_seqlens)  // packed batch: the whole tiles of each sequence
+    return !dense && p.head_dim == 128 && p.block_size >= 64 && p.q_row0 == 0 && p.q_rows >= kFwdBM;
+  return p.head_dim == 128 && (dense || p.block_size >= 64) && p.q_rows % 128 == 0 && p.q_row0 % 128 == 0;
 }
 
 hipError_t launch_fwd_pipe(const AttnParams& p, bool dense, hipStream_t stream) {
   const int grid = grid_for(p.batch * p.heads, p.q_rows / kFwdBM);
-  if (dense)
+  if (p.cu_seqlens)
+    hipLaunchKernelGGL((fwd_pipe_kernel<128, false, true>), dim3(grid), dim3(kThreads), 0, stream, p);
+  else if (dense)
     hipLaunchKernelGGL((fwd_pipe_kernel<128, true>), dim3(grid), dim3(kThreads), 0, stream, p);
   else
     hipLaunchKernelGGL((fwd_pipe_kernel<128, false>), dim3(grid), dim3(kThreads), 0, stream, p);

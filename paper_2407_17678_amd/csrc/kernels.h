@@ -36,6 +36,10 @@ struct AttnParams {
   // sequence b owns rows cu_seqlens[b] .. cu_seqlens[b+1]-1 of q, k, v, o and lse; then batch is
   // the number of sequences, seqlen the rows in the tensors and q_rows the longest length allowed
   const int32_t* cu_seqlens;
+  // packed batch, set by the launch code: 0 = the launch covers every 128-row tile of every sequence;
+  // 1 = only each sequence's last tile, and only where that tile is a partial one (the tiles before it
+  // are then computed by the fast-path kernel, which takes whole tiles only)
+  int varlen_tail;
   int64_t q_sb, q_sh, q_st;
   int64_t kv_sb, kv_sh, kv_st;
   float scale;        // softmax scale
@@ -79,16 +83,17 @@ struct DecodeParams {
 
 // Each returns the hipError_t of the launch (hipGetLastError after the launch).
 hipError_t launch_fwd(const AttnParams& p, bool dense, hipStream_t stream);
-// The forward's fast path (head_dim 128, mask blocks of 64 or 128 tokens, whole 128-row tiles):
-// whether it covers a call, and its launch.  launch_fwd uses it where it applies.
+// The forward's fast path (head_dim 128, mask blocks of 64 or 128 tokens, whole 128-row tiles; of a
+// packed batch the whole tiles of each sequence): whether it covers a call, and its launch.  launch_fwd
+// uses it where it applies.
 bool fwd_pipe_applies(const AttnParams& p, bool dense);
 hipError_t launch_fwd_pipe(const AttnParams& p, bool dense, hipStream_t stream);
 // `stages` selects which of the three backward launches run: 1 = delta, 2 = dK/dV, 4 = dQ.
 constexpr int kBwdDelta = 1, kBwdDkDv = 2, kBwdDq = 4, kBwdAll = 7;
 hipError_t launch_bwd(const AttnParams& p, bool dense, int stages, hipStream_t stream);
-// The dQ launch's fast path (head_dim 128, mask blocks of 64 or 128 tokens, whole 128-row tiles of a
-// fixed-length batch; it also leaves delta and base-2 LSE in the workspace): whether it covers a call,
-// and its launch.  launch_bwd uses it where it applies.
+// The dQ launch's fast path (head_dim 128, mask blocks of 64 or 128 tokens, whole 128-row tiles - of a
+// packed batch the whole tiles of each sequence; it also leaves delta and base-2 LSE in the workspace):
+// whether it covers a call, and its launch.  launch_bwd uses it where it applies.
 bool dq_pipe_applies(const AttnParams& p, bool dense);
 hipError_t launch_dq_pipe(const AttnParams& p, bool dense, hipStream_t stream);
 // The dQ launch of the backward that keeps dS: dQ = scale * dS K over the stored units.
