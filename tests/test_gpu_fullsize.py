@@ -257,7 +257,10 @@ def test_7b_prefill_varlen_full():
     rng = np.random.default_rng(4)
     for sq, L in enumerate(lens.tolist()):
         lo = int(cu[sq])
-        rows = sorted({0, S - 1, S, L // 2, (L // S) * S - 1, min((L // S) * S, L - 1), L - 2, L - 1} |
+        # (whole 128-row tiles and the partial last tile are computed by different kernels: both sides of
+        # that line are in the sample)
+        rows = sorted({0, S - 1, S, L // 2, (L // S) * S - 1, min((L // S) * S, L - 1), L - 2, L - 1,
+                       (L // 128) * 128 - 1, min((L // 128) * 128, L - 1)} |
                       set(int(x) for x in rng.integers(0, L, size=6)))
         rows = np.array([r for r in rows if 0 <= r < L])
         for h in (int(rng.integers(0, H)), (5 * sq + 3) % H):
