@@ -116,3 +116,27 @@ def test_varlen_backward_agrees_with_the_fixed_length_backward():
         torch.cuda.synchronize()
         for n, t in zip(("dq", "dk", "dv"), d1):
             assert G.rel_l2(G.to_f64(t), G.to_f64(out[n][:, :, lo:lo + L])) <= 5e-3, (sq, n)
+
+
+def test_varlen_seeded_sweep_around_the_tile_size():
+    """Random packed batches for head_dim 128 and blocks of 64 and 128 tokens, lengths drawn around the
+    multiples of 128: whole 128-row tiles and a sequence's partial last tile are computed by different
+    kernels (forward and dQ alike), so lengths of exactly k * 128, one more, one less, below 128 and zero
+    all occur, with random local-window and stride parameters."""
+    rng = np.random.default_rng(2024)
+    for case in range(10):
+        S = int(rng.choice([64, 128]))
+        H = int(rng.integers(1, 4))
+        Bk = int(rng.integers(2, 9)) * (2 if S == 64 else 1)
+        max_len = Bk * S
+        lens = []
+        for _ in range(int(rng.integers(2, 7))):
+            base = int(rng.integers(0, max_len // 128 + 1)) * 128
+            lens.append(int(np.clip(base + int(rng.choice([-1, 0, 0, 1, 5, -37, 64])), 0, max_len)))
+        lens.append(int(rng.integers(0, 128)))
+        w = dataclasses.replace(synth.WORKLOADS["1p3b_8k"], block_size=S, local_blocks=int(rng.integers(1, 4)),
+                                stride=int(rng.integers(0, 5)))
+        print("varlen sweep case", case, "S", S, "H", H, "B", Bk, "local", w.local_blocks, "stride", w.stride, "lens", lens,
+              flush=True)
+        bits, cu, M, out = _run(w, H, lens, Bk, extra_rows=int(rng.integers(0, 70)))
+        _check(bits, cu, M, S, w.scale, out, int(cu[-1]))
