@@ -48,3 +48,21 @@ def test_bench_times_both_forms_of_the_backward():
     rec, keep = d["backward_recomputing"], d["backward_keeping_ds"]
     assert keep["workspace_bytes"] > rec["workspace_bytes"] and rec["ms"] > 0 and keep["ms"] > 0
     assert d["backward_path"] == ("keeping dS" if keep["ms"] < rec["ms"] else "recomputing")
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("workload,kernel,unit", [("7b_prefill_varlen", "fwd_pipe_kernel", "TFLOP/s"),
+                                                  ("7b_decode", "decode_split_kernel", "GB/s")])
+def test_bench_lines_of_the_serving_workloads(workload, kernel, unit):
+    # the packed prefill batch (two launches per call: their traffic figures are summed) and the decode batch
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", workload, "--steps", "2",
+                        "--warmup", "1", "--no-cpu-baseline"], capture_output=True, text=True, timeout=600, cwd=ROOT)
+    assert r.returncode == 0, r.stderr[-2000:]
+    out = json.loads(r.stdout.strip().splitlines()[-1])
+    assert out["unit"] == unit and out["value"] > 0 and out["n_gpus"] == 1 and out["steps"] == 2
+    roof = out["roofline"]
+    assert kernel in roof["kernel"] and 0 < roof["frac"] < 1
+    # the committed counter summary, when it was taken on these kernel sources; else null, never a stale figure
+    assert roof["traffic"] is None or roof["traffic"] > 1e8
+    if workload == "7b_prefill_varlen":
+        assert out["config"]["tflops_fwd_bwd"] > 0 and out["config"]["speedup_vs_padded"] > 1
