@@ -140,3 +140,44 @@ def test_varlen_seeded_sweep_around_the_tile_size():
               flush=True)
         bits, cu, M, out = _run(w, H, lens, Bk, extra_rows=int(rng.integers(0, 70)))
         _check(bits, cu, M, S, w.scale, out, int(cu[-1]))
+
+
+def test_varlen_row_offsets_that_make_no_sense_stay_inside_the_tensors():
+    """cu_seqlens is a device array the host cannot check: negative entries, entries far beyond the tensors,
+    decreasing ones.  The kernels cut every sequence to the rows that exist and to max_seqlen, so such a call
+    must complete, leave the rows no (cut) sequence owns alone, and still compute the sequences that are in
+    order and overlap nothing - forward and backward, on the path with the whole-tile kernels."""
+    w = dataclasses.replace(synth.WORKLOADS["1p3b_8k"], local_blocks=2, stride=3)
+    H, Bk, S, D = 2, 8, w.block_size, w.head_dim
+    total, max_len = 1600, Bk * S
+    big = 2_000_000_000
+    cu = np.array([-big, -3, 600, 900, big, 1450, 1500, 1600], dtype=np.int32)
+    # as the kernels read it: rows 0..511 (twice), 600..899, 900..1411, nothing, 1450..1499, 1500..1599
+    valid = [(600, 300), (1450, 50), (1500, 100)]
+    qb, kb, vb, gb = synth.train_inputs(w, heads=H, batch=1, seqlen=total)
+    M = orc.block_mask(H, Bk, w.local_blocks, w.stride)
+    lay = B.s2_layout_build(B.layout_params(H, Bk, S, w.local_blocks, w.stride))
+    q, k, v, g = G.to_dev(qb), G.to_dev(kb), G.to_dev(vb), G.to_dev(gb)
+    sent = lambda: torch.full_like(q.view(torch.int16), SENTINEL).view(q.dtype)
+    o, dq, dk, dv = sent(), sent(), sent(), sent()
+    lse = torch.full((H, total), 77.0, dtype=torch.float32, device="cuda")
+    cud = torch.from_numpy(cu).cuda()
+    ws = torch.zeros(B.s2_attn_bwd_varlen_workspace_bytes(H, total, D), dtype=torch.uint8, device="cuda")
+    print("varlen case with senseless row offsets", cu.tolist(), flush=True)
+    B.s2_attn_fwd_varlen(lay, q, k, v, o, lse, cud, max_len, w.scale)
+    B.s2_attn_bwd_varlen(lay, q, k, v, o, lse, g, dq, dk, dv, cud, max_len, w.scale, ws)
+    torch.cuda.synchronize()
+    f = G.bits_f64
+    for lo, L in valid:
+        for h in range(H):
+            sl = lambda x: f(x)[0, h, lo:lo + L]
+            dQ, dK, dV, O, LSE = orc.attention_backward_head(sl(qb), sl(kb), sl(vb), sl(gb), M[h], S, w.scale)
+            assert G.o_excess(G.to_f64(o)[0, h, lo:lo + L], O) <= 0, (lo, h)
+            assert np.abs(G.to_f64(lse)[h, lo:lo + L] - LSE).max() <= LSE_TOL, (lo, h)
+            for n, got, ref in (("dq", dq, dQ), ("dk", dk, dK), ("dv", dv, dV)):
+                assert G.rel_l2(G.to_f64(got)[0, h, lo:lo + L], ref) <= GRAD_TOL, (n, lo, h)
+    for t in (o, dq, dk, dv):
+        # rows 512..599 and 1412..1449 belong to no sequence as the kernels cut them
+        assert (t.view(torch.int16)[0, :, 512:600] == SENTINEL).all()
+        assert (t.view(torch.int16)[0, :, 1412:1450] == SENTINEL).all()
+        assert torch.isfinite(t[0, :, :512].float()).all() and torch.isfinite(t[0, :, 900:1412].float()).all()
